@@ -1,0 +1,100 @@
+"""Shared test scaffolding: builds seeded cases on the CPU with the oracle.
+
+Everything here is host-side numpy.  Pools are filled with ``oracle.scatter`` (or, where a
+test wants independence from it, with numpy reshapes), so the GPU path never produces an
+input or an expected value.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+import oracle
+from paper_2602_22593_amd import workloads as wl
+
+
+def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> float64, exact."""
+    return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def geometry(w: wl.Workload) -> oracle.Geometry:
+    return oracle.Geometry(w.n_q_heads, w.n_kv_heads, w.head_dim, w.base_block_size)
+
+
+@dataclass
+class Case:
+    w: wl.Workload
+    geom: oracle.Geometry
+    view: oracle.View
+    info: dict
+    ctx: np.ndarray          # int32[batch]
+    seq_off: np.ndarray      # int64[batch+1]
+    K: np.ndarray            # uint16[total][Hkv][d]
+    V: np.ndarray
+    q_full: np.ndarray       # uint16[batch][Hq][d]
+    q: np.ndarray            # uint16[batch][Hql][d]  (rank's slice)
+    table: np.ndarray        # int32[batch][cols]
+    pool: np.ndarray         # uint16[n_blocks][block_elems]
+
+
+def q_slice(q_full: np.ndarray, info: dict, rank: int) -> np.ndarray:
+    """Query heads of rank r: the contiguous range [r*Hql, (r+1)*Hql) (paper Sec. 4.1.1)."""
+    hql = info["n_q_local"]
+    return np.ascontiguousarray(q_full[:, rank * hql:(rank + 1) * hql, :])
+
+
+def make_case(w: wl.Workload, view_triple, ctx: Optional[np.ndarray] = None, slack: float = 1.2,
+              n_pool_blocks: Optional[int] = None, K=None, V=None, q_full=None) -> Case:
+    geom = geometry(w)
+    view = oracle.View(geom, *view_triple)
+    info = view.query()
+    ctx = wl.draw_ctx_lens(w) if ctx is None else np.asarray(ctx, dtype=np.int32)
+    w_eff = w if len(ctx) == w.batch else wl.Workload(w.name, w.index, w.n_q_heads, w.n_kv_heads,
+                                                       w.head_dim, w.base_block_size, len(ctx),
+                                                       w.lengths, w.views)
+    if K is None:
+        K, V = wl.logical_kv(w_eff, ctx)
+    if q_full is None:
+        q_full = wl.queries(w_eff)
+    need = int(wl.blocks_needed(ctx, info["block_tokens"]).sum())
+    g = wl.generator(w.index, wl.SUB_PERM)
+    if n_pool_blocks is None:
+        perm = wl.shuffled_pool(max(need, 1), slack, g)
+    else:
+        import torch
+        perm = torch.randperm(n_pool_blocks, generator=g).numpy().astype(np.int32)
+    table, _ = wl.assign_blocks(ctx, info["block_tokens"], perm)
+    pool = wl.poisoned_pool(len(perm), info["block_bytes"] // 2)
+    seq_off = wl.seq_offsets(ctx)
+    oracle.scatter(view, pool, table, ctx, seq_off, K, V)
+    return Case(w_eff, geom, view, info, ctx, seq_off, K, V, q_full,
+                q_slice(q_full, info, view.rank), table, pool)
+
+
+def textbook_attention(q_full: np.ndarray, K: np.ndarray, V: np.ndarray, seq_off: np.ndarray,
+                       n_q_heads: int, n_kv_heads: int, scale: float) -> np.ndarray:
+    """softmax(scale * q K^T) V per sequence and head with numpy matmuls, fp64.
+
+    The textbook single-query attention on the logical (un-paged) tensors; query head h
+    reads KV head h // (Hq // Hkv).
+    """
+    batch, hq, d = q_full.shape
+    G = n_q_heads // n_kv_heads
+    qf = bf16_bits_to_f64(q_full)
+    Kf = bf16_bits_to_f64(K)
+    Vf = bf16_bits_to_f64(V)
+    out = np.zeros((batch, hq, d))
+    for s in range(batch):
+        a, b = int(seq_off[s]), int(seq_off[s + 1])
+        if b == a:
+            continue
+        for h in range(hq):
+            g = h // G
+            logits = (Kf[a:b, g, :] @ qf[s, h, :]) * scale
+            p = np.exp(logits - logits.max())
+            p = p / p.sum()
+            out[s, h, :] = p @ Vf[a:b, g, :]
+    return out
