@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: paged decode attention through a layout view
+(KV bytes/s against the HBM roofline, microseconds per layer) and kv_repack GB/s.
+
+A step is one paged_decode_attn call (main kernel + split-KV merge) over one batch of the
+workload, inputs resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def ensure_built():
+    from paper_2602_22593_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2602_22593_amd.build import build
+        build()
+
+
+def cpu_baseline(case, target_seconds=10.0):
+    """The oracle as it stands, timed on the host cores on the same inputs (pool copy 0)."""
+    import numpy as np
+    import oracle
+    w = case.workload
+    view = oracle.View(oracle.Geometry(w.n_q_heads, w.n_kv_heads, w.head_dim, w.base_block_size),
+                       *case.triple)
+    pool = case.pools[0].view(dtype=__import__("torch").int16).cpu().numpy().view(np.uint16)
+    q = case.q.view(dtype=__import__("torch").int16).cpu().numpy().view(np.uint16)
+    table, ctx = case.tables[0], case.ctx
+    threads = oracle.num_threads()
+    reps, spent = 0, 0.0
+    while reps < 8 and spent < target_seconds:
+        t0 = time.perf_counter()
+        ref = oracle.paged_decode(view, q, pool, table, ctx)
+        spent += time.perf_counter() - t0
+        reps += 1
+    return {
+        "value": round(case.kv_bytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": threads,
+        "kind": "oracle",
+        "sample": f"all {len(ctx)} sequences of the workload, {reps} full passes, "
+                  f"{spent / reps:.2f} s per pass (fp64, OpenMP over (sequence, query head))",
+    }, ref
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_dp_b64")
+    ap.add_argument("--view", default=None, help="layout,p,r (default: the workload's first view)")
+    ap.add_argument("--copies", type=int, default=4, help="independent pools cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip repack and the other workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    ensure_built()
+    import numpy as np
+    import torch
+    from paper_2602_22593_amd import binding as kv
+    from paper_2602_22593_amd import harness, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    triple = tuple(int(x) for x in args.view.split(",")) if args.view else w.views[0]
+
+    case = harness.build_decode_case(w, triple, n_copies=args.copies)
+    run = case.prepared()
+
+    # --- timed region: exactly K steps between two synchronisations ---------------------------
+    for i in range(args.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run(args.warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    gbps = case.kv_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # --- per-kernel durations from HIP events on the launch stream (separate pass) -------------
+    kv.kv_profile_enable(True)
+    for i in range(args.steps):
+        run(i)
+    torch.cuda.synchronize()
+    main_ms, n_main = kv.kv_profile_read(kv.KV_PROF_DECODE_MAIN)
+    merge_ms, n_merge = kv.kv_profile_read(kv.KV_PROF_DECODE_MERGE)
+    kv.kv_profile_enable(False)
+    main_avg_ms = main_ms / max(n_main, 1)
+    achieved = case.kv_bytes / (main_avg_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{w.name}:{','.join(map(str, triple))}")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "decode-attn KV bytes/s", "value": round(gbps, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_layer": round(ms_per_step * 1e3, 2),
+        "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 K/V/q/out, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "view": {"layout": "DP" if triple[0] == 0 else "TP",
+                                                "tp_degree": triple[1], "rank": triple[2]},
+                   "n_q_local": case.view.n_q_local, "n_kv_local": case.view.n_kv_local,
+                   "head_dim": w.head_dim, "block_tokens": case.view.block_tokens,
+                   "batch": w.batch, "tokens": int(case.ctx.sum()), "kv_bytes": case.kv_bytes,
+                   "pool_copies": args.copies,
+                   "chunk_tokens": kv.kv_get_option("chunk_tokens")},
+        "roofline": {"bound": "hbm", "kernel": "paged decode main kernel",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "avg_kernel_us": round(main_avg_ms * 1e3, 2),
+                     "merge_kernel_us": round(merge_ms / max(n_merge, 1) * 1e3, 2),
+                     "algorithmic_bytes_per_launch": case.kv_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        base, ref = cpu_baseline(case)
+        result["cpu_baseline"] = base
+        # the timed configuration must also be right: compare against the oracle's output
+        out = case.run(0)
+        torch.cuda.synchronize()
+        got = (out.view(dtype=torch.int16).cpu().numpy().view(np.uint16).astype(np.uint32) << 16) \
+            .view(np.float32).astype(np.float64)
+        err = np.abs(got - ref)
+        result["parity_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                                      "ok": bool(err.max() <= 2e-2 and err.mean() <= 2e-3)}
+
+    if not args.no_extras:
+        extras = {}
+        del case, run
+        torch.cuda.empty_cache()
+        # kv_repack: the 8B batch-128 lengths, DP layout -> rank-0 TP4 layout and back
+        rw = wl.WORKLOADS["llama8b_tp_b128"]
+        rc = harness.build_repack_case(rw, (0, 1, 0), (1, 4, 0))
+        steps = max(5, args.steps // 5)
+        kv.kv_profile_enable(True)
+        fwd_ms = harness.time_calls(lambda i: rc.forward(), steps, 3)
+        f_ms, f_n = kv.kv_profile_read(kv.KV_PROF_REPACK)
+        bwd_ms = harness.time_calls(lambda i: rc.backward(), steps, 3)
+        b_ms, b_n = kv.kv_profile_read(kv.KV_PROF_REPACK)
+        kv.kv_profile_enable(False)
+        extras["kv_repack"] = {
+            "workload": rw.name, "moved_bytes": rc.moved_bytes,
+            "dp_to_tp4_r0": {"us": round(fwd_ms * 1e3, 2),
+                             "read_plus_write_GBps": round(2 * rc.moved_bytes / (fwd_ms * 1e-3) / 1e9, 1),
+                             "kernel_us": round(f_ms / max(f_n, 1) * 1e3, 2)},
+            "tp4_r0_to_dp": {"us": round(bwd_ms * 1e3, 2),
+                             "read_plus_write_GBps": round(2 * rc.moved_bytes / (bwd_ms * 1e-3) / 1e9, 1),
+                             "kernel_us": round(b_ms / max(b_n, 1) * 1e3, 2)},
+        }
+        del rc
+        torch.cuda.empty_cache()
+        others = []
+        for name in ("llama8b_tp_b128", "llama70b_tp8_b256", "llama8b_tp4_longmix"):
+            ow = wl.WORKLOADS[name]
+            for tr in ow.views:
+                oc = harness.build_decode_case(ow, tr, n_copies=args.copies)
+                orun = oc.prepared()
+                ms = harness.time_calls(orun, max(10, args.steps // 2), 5)
+                others.append({"workload": name, "view": list(tr), "us_per_layer": round(ms * 1e3, 2),
+                               "GBps": round(oc.kv_bytes / (ms * 1e-3) / 1e9, 1),
+                               "pct_hbm_peak": round(100 * oc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)})
+                del oc, orun
+                torch.cuda.empty_cache()
+        extras["other_workloads"] = others
+        result["extras"] = extras
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

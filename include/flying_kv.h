@@ -1,0 +1,219 @@
+/*
+ * flying_kv.h -- C ABI of the MI355X (gfx950) paged decode attention / KV repack library.
+ *
+ * The library implements the device side of the paper's KV Cache Adaptor (Sec. 4.2): one
+ * physical pool of constant-size KV blocks that is read either as a DP replica's blocks
+ * (all KV heads, B_base tokens per block) or as one TP rank's blocks (H/p heads,
+ * p * B_base tokens per block), the attention kernel being told "the stride and capacity
+ * for the specific request" (Sec. 4.2.3).  On top of that contract it provides the decode
+ * attention kernel, a block repack kernel for the transitions where bytes must move (the
+ * paper recomputes the cache there, Sec. 5.2.2), and the KV append kernel.
+ *
+ * Conventions
+ *   - Every function returns 0 (KV_OK) or a negative kv_status.  Nothing throws, nothing
+ *     synchronises the stream, nothing allocates device memory.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library owns only kv_view objects (host).
+ *   - bf16 everywhere in memory; all accumulation is fp32 on the device.
+ *   - Physical layout of the pool: n_pool_blocks blocks of block_bytes each.  A block read
+ *     under a view with capacity Bv (tokens) and Hrow KV heads per token row is the array
+ *         bf16 [2 (0 = K, 1 = V)] [Bv] [Hrow] [head_dim]
+ *     and Bv * Hrow = base_block_size * n_kv_heads for every view, so block_bytes
+ *     = 2 * base_block_size * n_kv_heads * head_dim * 2 never changes (Eq. 2 held constant).
+ *   - Token t of sequence s lives in block block_table[s][t / Bv], slot t % Bv.
+ */
+#ifndef FLYING_KV_H
+#define FLYING_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KV_OK = 0,
+    KV_ERR_INVALID_ARG = -1, /* null pointer, negative size, impossible view parameters      */
+    KV_ERR_UNSUPPORTED = -2, /* valid in principle, not built (dtype, head_dim, group size)   */
+    KV_ERR_WORKSPACE = -3,   /* workspace smaller than paged_decode_attn_workspace_bytes()   */
+    KV_ERR_HIP = -4,         /* a HIP call or kernel launch failed; see kv_last_hip_error()   */
+    KV_ERR_RANGE = -5,       /* kv_validate_tables: block id outside [0, n_pool_blocks)       */
+    KV_ERR_ALIAS = -6        /* kv_validate_tables: a block appears twice / src meets dst     */
+} kv_status;
+
+/* Model-side constants (Alg. 1 "Require": B_base, H_base) plus the attention shape. */
+typedef struct {
+    int32_t n_q_heads;       /* total query heads of the layer (before any TP split)          */
+    int32_t n_kv_heads;      /* total KV heads H_base                                          */
+    int32_t head_dim;        /* elements per head; supported: 64, 128                          */
+    int32_t base_block_size; /* B_base: tokens per block in DP mode                            */
+    int32_t dtype;           /* 0 = bf16 (the only one)                                        */
+} kv_geometry;
+
+/* How the rows of a block are physically arranged. */
+typedef enum {
+    KV_LAYOUT_DP = 0, /* [B_base tokens][all H_base heads][d]                                  */
+    KV_LAYOUT_TP = 1  /* [p * B_base tokens][H_base / p heads][d]  (Eq. 3, Eq. 4)              */
+} kv_layout;
+
+typedef struct kv_view kv_view; /* opaque, immutable, host memory */
+
+/*
+ * kv_view_create -- resolve (layout, tp_degree p, rank r) over a geometry (Eq. 3:
+ * B(p) = p * B_base; Alg. 1 step 4 / Eq. 4: H_req = H_base / N_eng; Sec. 4.1.1: rank r owns
+ * the r-th contiguous slice of heads, KV heads [r*H/p, (r+1)*H/p) and the query heads of
+ * those groups).
+ *   KV_LAYOUT_DP, p = 1, r = 0 : the DP replica view, all heads.
+ *   KV_LAYOUT_TP, p, r         : rank r's blocks in the TP arrangement.
+ *   KV_LAYOUT_DP, p > 1, r     : rank r's head slice read in place from DP-arranged blocks
+ *                                (strided rows, no bytes moved).
+ * Errors: KV_ERR_INVALID_ARG for null pointers, p < 1, r outside [0, p), p not dividing
+ * n_kv_heads or n_q_heads, n_kv_heads not dividing n_q_heads, non-positive sizes, head_dim
+ * not a multiple of 8, unknown layout; KV_ERR_UNSUPPORTED for dtype != 0.
+ * *out is written only on success; release it with kv_view_destroy.
+ */
+int kv_view_create(const kv_geometry* geometry, int layout, int tp_degree, int rank,
+                   kv_view** out);
+void kv_view_destroy(kv_view* view);
+
+/*
+ * kv_view_query -- read back what the view resolved to.  Any output pointer may be null.
+ * block_tokens = B(p) (capacity), n_kv_local = KV heads exposed, n_q_local = query heads
+ * exposed, kv_head0 = first global KV head exposed, block_bytes = constant block size.
+ */
+int kv_view_query(const kv_view* view, int32_t* block_tokens, int32_t* n_kv_local,
+                  int32_t* n_q_local, int32_t* kv_head0, int64_t* block_bytes);
+
+/*
+ * kv_view_strides -- the "stride" half of the per-request kernel parameters (Sec. 4.2.3):
+ * elements between consecutive tokens of a block (row_heads * head_dim), KV heads stored
+ * per token row, and the position of the first exposed head inside a row.
+ */
+int kv_view_strides(const kv_view* view, int32_t* token_stride_elems, int32_t* row_heads,
+                    int32_t* row_head0);
+
+/*
+ * paged_decode_attn -- one decode step of attention for a batch (Sec. 2.1: attention over
+ * the cached keys and values; Sec. 4.2.2: KV blocks found through the logical table):
+ *     out[s][i][:] = sum_t softmax_t(scale * q[s][i] . K[s][t][i / G]) * V[s][t][i / G]
+ * for t in [0, ctx_lens[s]), local query head i in [0, n_q_local), G = n_q_heads /
+ * n_kv_heads.  No mask other than t < ctx_lens[s].
+ *
+ *   q            device, bf16 [batch][n_q_local][head_dim]     (read)
+ *   out          device, bf16 [batch][n_q_local][head_dim]     (written; rows with
+ *                ctx_lens[s] == 0 are written as zeros)
+ *   kv_pool      device, the block pool described above         (read only)
+ *   n_pool_blocks  number of blocks in the pool (host check of sizes only)
+ *   block_table  device, int32 [batch][block_table_stride]; entries at index >=
+ *                ceil(ctx_lens[s] / block_tokens) are never read for effect (may be -1)
+ *   ctx_lens     device, int32 [batch], each in [0, max_ctx_len]
+ *   max_ctx_len  host upper bound of ctx_lens (sizes the launch; a larger bound is legal,
+ *                a smaller one makes the result undefined)
+ *   scale        softmax scale; <= 0 selects 1 / sqrt(head_dim)
+ *   workspace    device scratch of at least paged_decode_attn_workspace_bytes(view, batch,
+ *                max_ctx_len) bytes, 256-byte aligned; contents need not be initialised
+ *                and are undefined afterwards
+ *   hip_stream   hipStream_t to launch on (null = default stream)
+ *
+ * Block ids inside [0, n_pool_blocks) for every valid token are a precondition (not
+ * checked on the hot path; see kv_validate_tables).
+ * Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, block_table_stride too small
+ * for max_ctx_len), KV_ERR_UNSUPPORTED (head_dim or group size without a kernel),
+ * KV_ERR_WORKSPACE, KV_ERR_HIP.
+ */
+size_t paged_decode_attn_workspace_bytes(const kv_view* view, int batch, int max_ctx_len);
+int paged_decode_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
+                      const int32_t* block_table, int64_t block_table_stride,
+                      const int32_t* ctx_lens, int batch, int max_ctx_len,
+                      const kv_view* view, float scale, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/*
+ * kv_repack -- move KV rows between two arrangements inside one pool, bit-exactly.  This
+ * is what a DP->TP or TP->DP transition needs when the existing blocks cannot simply be
+ * re-interpreted (the paper's Soft Preempt recomputes the cache instead, Sec. 5.2.2; a
+ * group dissolved under load, Sec. 2.3 use case 1, needs the reverse direction).
+ * For every sequence s, token t < n_tokens[s], plane (K, V) and every global KV head
+ * exposed by BOTH views, the head_dim-element row is copied from its address under
+ * src_view (through src_block_table) to its address under dst_view (through
+ * dst_block_table).  Every other byte of the pool keeps its value.
+ *
+ *   kv_pool          device, read and written
+ *   src_block_table  device, int32 [n_seqs][src_stride]
+ *   dst_block_table  device, int32 [n_seqs][dst_stride]
+ *   n_tokens         device, int32 [n_seqs], each in [0, max_tokens]
+ *   max_tokens       host upper bound of n_tokens (sizes the launch)
+ *
+ * Preconditions (not checked on the hot path): block ids in range; the source and the
+ * destination block sets are disjoint (an in-place repack is not defined).
+ * Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, views over different
+ * geometries, strides too small for max_tokens), KV_ERR_HIP.
+ */
+int kv_repack(void* kv_pool, int64_t n_pool_blocks, const kv_view* src_view,
+              const kv_view* dst_view, const int32_t* src_block_table, int64_t src_stride,
+              const int32_t* dst_block_table, int64_t dst_stride, const int32_t* n_tokens,
+              int n_seqs, int max_tokens, void* hip_stream);
+
+/*
+ * kv_append -- the "KV cache kernel" of Sec. 4.2.3: write the new token's K and V rows of
+ * every sequence into the pool at position positions[s] (normally the current context
+ * length), using the view's stride and capacity.
+ *
+ *   k_new, v_new  device, bf16 [n_seqs][n_kv_local][head_dim]
+ *   positions     device, int32 [n_seqs]; a negative position skips the sequence
+ * Errors: KV_ERR_INVALID_ARG, KV_ERR_HIP.
+ */
+int kv_append(void* kv_pool, int64_t n_pool_blocks, const kv_view* view, const void* k_new,
+              const void* v_new, const int32_t* block_table, int64_t block_table_stride,
+              const int32_t* positions, int n_seqs, void* hip_stream);
+
+/*
+ * kv_validate_tables -- debugging aid, NOT for the hot path: copies the tables to the host
+ * (synchronises the stream) and checks that every block id a valid token needs lies in
+ * [0, n_pool_blocks) (KV_ERR_RANGE) and that no block is used twice within the table
+ * (KV_ERR_ALIAS).  With other_table != null also checks that the two tables share no
+ * block (repack precondition).  other_* describe the second table under other_view.
+ */
+int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t* block_table,
+                       int64_t block_table_stride, const int32_t* n_tokens, int n_seqs,
+                       const kv_view* other_view, const int32_t* other_table,
+                       int64_t other_stride, void* hip_stream);
+
+/* Tunables for experiments: "chunk_tokens" (split-KV granularity, 0 = automatic).
+ * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
+int kv_set_option(const char* key, int64_t value);
+int64_t kv_get_option(const char* key);
+
+/*
+ * Measurement aid (not part of the method).  While enabled, paged_decode_attn and kv_repack
+ * bracket each of their kernels with HIP events recorded on the caller's stream, so that a
+ * benchmark can read per-kernel durations without an external profiler.
+ *   kv_profile_enable(on)  : 1 = start recording (drops earlier records), 0 = stop.
+ *   kv_profile_read(which, &total_ms, &n) : synchronises on the recorded events, returns the
+ *       summed duration and the number of launches of kernel `which` since enabling, and
+ *       clears them.  which: 0 = decode main kernel, 1 = decode merge kernel, 2 = repack kernel.
+ * Not thread-safe; at most 4096 launches per kernel are kept between reads.
+ */
+enum { KV_PROF_DECODE_MAIN = 0, KV_PROF_DECODE_MERGE = 1, KV_PROF_REPACK = 2, KV_PROF_KINDS = 3 };
+int kv_profile_enable(int on);
+int kv_profile_read(int which, double* total_ms, int64_t* n_launches);
+
+/*
+ * Streaming kernels of known traffic (measurement aids, not part of the method): read `bytes`
+ * once (kv_probe_read) or copy them once (kv_probe_copy) with n_workgroups workgroups of 256
+ * lanes, 16 bytes per lane per access.  They give the achievable HBM rate on the box and the
+ * reference against which profiler byte counters are scaled.  src/dst/sink are device
+ * pointers, bytes a multiple of 16; sink may be null.
+ */
+int kv_probe_read(const void* src, size_t bytes, void* sink, int n_workgroups, void* hip_stream);
+int kv_probe_copy(void* dst, const void* src, size_t bytes, int n_workgroups, void* hip_stream);
+
+const char* kv_strerror(int status);   /* static string, never null */
+const char* kv_last_hip_error(void);   /* text of the last HIP failure seen by this thread */
+const char* kv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLYING_KV_H */

@@ -1,0 +1,87 @@
+// Internal definitions shared by the translation units of libflyingkv (never installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flying_kv.h"
+
+#define KV_VIEW_MAGIC 0x4b565657u
+
+// 16-byte register vector (four dwords), the unit of every KV load and store.
+typedef uint32_t kv_u32x4 __attribute__((ext_vector_type(4)));
+
+// Host-side resolved view (Eq. 3 / Eq. 4 of the paper and the head partition of Sec. 4.1.1).
+struct kv_view {
+    uint32_t magic;
+    kv_geometry geom;
+    int32_t layout, p, r;
+    int32_t block_tokens;  // Bv: capacity of a block under this view
+    int32_t row_heads;     // KV heads stored in one token row of a block
+    int32_t n_kv_local;    // KV heads exposed
+    int32_t n_q_local;     // query heads exposed
+    int32_t kv_head0;      // first global KV head exposed
+    int32_t row_head0;     // where that head sits in a token row
+    int32_t group;         // G = n_q_heads / n_kv_heads
+    int64_t plane_elems;   // base_block_size * n_kv_heads * head_dim
+    int64_t block_bytes;   // 2 planes * plane_elems * sizeof(bf16)
+};
+
+// What a kernel needs to know about a view; passed by value as a kernel argument.
+struct kv_view_dev {
+    int32_t block_tokens;      // Bv
+    int32_t block_shift;       // log2(Bv) if Bv is a power of two, else -1
+    int32_t token_stride;      // elements between consecutive tokens of a block
+    int32_t head_off;          // elements from the start of a token row to the first exposed head
+    int32_t n_kv_local;
+    int32_t n_q_local;
+    int32_t head_dim;
+    int32_t kv_head0;
+    int64_t plane_elems;
+    int64_t block_elems;       // 2 * plane_elems
+};
+
+static inline kv_view_dev kv_view_to_dev(const kv_view* v)
+{
+    kv_view_dev d;
+    d.block_tokens = v->block_tokens;
+    d.block_shift = -1;
+    if ((v->block_tokens & (v->block_tokens - 1)) == 0) {
+        int s = 0;
+        while ((1 << s) < v->block_tokens) ++s;
+        d.block_shift = s;
+    }
+    d.token_stride = v->row_heads * v->geom.head_dim;
+    d.head_off = v->row_head0 * v->geom.head_dim;
+    d.n_kv_local = v->n_kv_local;
+    d.n_q_local = v->n_q_local;
+    d.head_dim = v->geom.head_dim;
+    d.kv_head0 = v->kv_head0;
+    d.plane_elems = v->plane_elems;
+    d.block_elems = 2 * v->plane_elems;
+    return d;
+}
+
+static inline bool kv_view_ok(const kv_view* v) { return v && v->magic == KV_VIEW_MAGIC; }
+
+// t -> (index into the block table row, slot inside the block)
+__device__ __forceinline__ void kv_split_token(const kv_view_dev& v, int t, int& j, int& slot)
+{
+    if (v.block_shift >= 0) {
+        j = t >> v.block_shift;
+        slot = t & (v.block_tokens - 1);
+    } else {
+        j = t / v.block_tokens;
+        slot = t - j * v.block_tokens;
+    }
+}
+
+int kv_record_hip_error(hipError_t e, const char* what);
+
+// Library-wide tunables (kv_set_option).
+int64_t kv_option_chunk_tokens();
+int64_t kv_option_force_kernel();
+
+// Per-kernel event brackets for kv_profile_*: begin returns a slot (or -1 when disabled).
+int kv_prof_begin(int which, hipStream_t st);
+void kv_prof_end(int which, int slot, hipStream_t st);

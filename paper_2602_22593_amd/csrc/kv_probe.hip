@@ -1,0 +1,65 @@
+// Trivial streaming kernels of known traffic: the measured HBM ceiling quoted next to the
+// published peak, and the reference against which profiler byte counters are scaled.
+#include "kv_internal.h"
+
+namespace {
+
+constexpr int kProbeThreads = 256;
+constexpr int kProbeUnroll = 8;
+
+// Every lane loads kProbeUnroll independent 16-byte pieces per trip, then folds them.
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const kv_u32x4* __restrict__ src,
+                                                                   size_t n_vec, uint32_t* sink)
+{
+    const size_t stride = (size_t)gridDim.x * kProbeThreads;
+    size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    kv_u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + (kProbeUnroll - 1) * stride < n_vec; i += kProbeUnroll * stride) {
+        kv_u32x4 v[kProbeUnroll];
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) acc ^= v[u];
+    }
+    for (; i < n_vec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    const uint32_t f = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (f == 0x9e3779b9u && sink) sink[0] = f;  // practically never: keeps the loads alive
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const kv_u32x4* __restrict__ src,
+                                                                   kv_u32x4* __restrict__ dst,
+                                                                   size_t n_vec)
+{
+    const size_t stride = (size_t)gridDim.x * kProbeThreads;
+    size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        kv_u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+    }
+    for (; i < n_vec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace
+
+extern "C" int kv_probe_read(const void* src, size_t bytes, void* sink, int n_workgroups,
+                             void* hip_stream)
+{
+    if (!src || bytes % 16 != 0 || n_workgroups <= 0) return KV_ERR_INVALID_ARG;
+    if (bytes == 0) return KV_OK;
+    hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)n_workgroups), dim3(kProbeThreads), 0,
+                       (hipStream_t)hip_stream, (const kv_u32x4*)src, bytes / 16, (uint32_t*)sink);
+    return kv_record_hip_error(hipGetLastError(), "kv_probe_read launch");
+}
+
+extern "C" int kv_probe_copy(void* dst, const void* src, size_t bytes, int n_workgroups,
+                             void* hip_stream)
+{
+    if (!src || !dst || bytes % 16 != 0 || n_workgroups <= 0) return KV_ERR_INVALID_ARG;
+    if (bytes == 0) return KV_OK;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)n_workgroups), dim3(kProbeThreads), 0,
+                       (hipStream_t)hip_stream, (const kv_u32x4*)src, (kv_u32x4*)dst, bytes / 16);
+    return kv_record_hip_error(hipGetLastError(), "kv_probe_copy launch");
+}

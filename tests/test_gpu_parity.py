@@ -1,0 +1,263 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
+seeded inputs.  Attention: max-abs <= 2e-2 and mean-abs <= 2e-3 (bf16 K/V/out, fp32
+accumulation); repack, append and table indexing: bit-exact on the whole pool."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import LAYOUT_DP, LAYOUT_TP
+from paper_2602_22593_amd import binding as kv
+from paper_2602_22593_amd import workloads as wl
+
+from helpers import bf16_bits_to_f64, geometry, make_case, q_slice
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+TINY = wl.WORKLOADS["tiny"]
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def require_gpu_and_library():
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    kv.lib()  # raises if the HIP library is not built: there is no fallback
+    yield
+    kv.kv_set_option("chunk_tokens", 0)
+
+
+def dev_u16(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a.view(np.int16)).to(DEV)
+
+
+def gpu_view(w, triple) -> kv.KVView:
+    return kv.kv_view_create(w.n_q_heads, w.n_kv_heads, w.head_dim, w.base_block_size, *triple)
+
+
+def run_gpu_decode(c, view, scale=0.0):
+    out = kv.paged_decode_attn(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                               torch.from_numpy(c.ctx).to(DEV), view,
+                               max_ctx_len=int(c.ctx.max()) if len(c.ctx) else 0, scale=scale)
+    torch.cuda.synchronize()
+    return bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
+
+
+def check_close(got, want, what=""):
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - want)
+    assert err.max() <= MAX_ABS, f"{what}: max-abs {err.max():.3e}"
+    assert err.mean() <= MEAN_ABS, f"{what}: mean-abs {err.mean():.3e}"
+
+
+@pytest.mark.parametrize("chunk", [0, 64, 128])
+@pytest.mark.parametrize("triple", [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 0), (LAYOUT_TP, 2, 1),
+                                    (LAYOUT_DP, 2, 1)])
+def test_tiny_config_all_views(triple, chunk):
+    """Tiny: 8 q heads, 2 KV heads, d 64, B_base 16, ctx {17, 64, 150, 300}; pool NaN-poisoned
+    outside the valid tokens.  chunk 64 / 128 force the split-KV + merge path."""
+    kv.kv_set_option("chunk_tokens", chunk)
+    c = make_case(TINY, triple, n_pool_blocks=128)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    got = run_gpu_decode(c, gpu_view(TINY, triple))
+    check_close(got, want, f"tiny {triple} chunk {chunk}")
+
+
+RAGGED = np.array([1, 15, 16, 17, 0, 511, 513, 1300, 2049, 64], dtype=np.int32)
+
+
+@pytest.mark.parametrize("chunk", [0, 256])
+@pytest.mark.parametrize("hq,hkv,triple", [
+    (32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 2, 1)), (32, 8, (LAYOUT_TP, 4, 3)),
+    (32, 8, (LAYOUT_TP, 8, 5)), (32, 8, (LAYOUT_DP, 4, 2)), (64, 8, (LAYOUT_TP, 8, 7)),
+    (64, 8, (LAYOUT_DP, 1, 0)), (16, 8, (LAYOUT_TP, 2, 0)), (8, 8, (LAYOUT_TP, 4, 1)),
+])
+def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk):
+    """Head dim 128 at the Llama shapes (G = 4, 8) and smaller groups (G = 2, 1): lengths that
+    span several tiles, end mid-block, are empty, or are exactly one block."""
+    kv.kv_set_option("chunk_tokens", chunk)
+    w = wl.Workload("ragged", 20 + hq // 8, hq, hkv, 128, 16, len(RAGGED), "x", ())
+    c = make_case(w, triple, RAGGED)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    got = run_gpu_decode(c, gpu_view(w, triple))
+    check_close(got, want, f"{hq}/{hkv} {triple} chunk {chunk}")
+    assert (got[4] == 0).all()                       # ctx_len 0 -> zeros
+    # ctx_len 1 -> the V row itself, exactly (bf16 in, bf16 out)
+    G = hq // hkv
+    for i in range(c.info["n_q_local"]):
+        g = c.info["kv_head0"] + i // G
+        assert np.array_equal(got[0, i], bf16_bits_to_f64(c.V[c.seq_off[0], g]))
+
+
+def test_explicit_scale_and_large_logits():
+    """A scale of 1.0 (8x the default at d = 64) makes the softmax nearly one-hot: checks the
+    running-max handling."""
+    c = make_case(TINY, (LAYOUT_TP, 2, 0))
+    for scale in (1.0, 0.01):
+        want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx, scale)
+        got = run_gpu_decode(c, gpu_view(TINY, (LAYOUT_TP, 2, 0)), scale)
+        check_close(got, want, f"scale {scale}")
+
+
+def test_non_power_of_two_block_size():
+    """B_base = 12 (capacity 24 at TP2): token -> (block, slot) needs a real division."""
+    w = wl.Workload("b12", 31, 8, 2, 64, 12, 3, "x", ())
+    ctx = np.array([11, 100, 313], dtype=np.int32)
+    for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)]:
+        c = make_case(w, triple, ctx)
+        want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+        check_close(run_gpu_decode(c, gpu_view(w, triple)), want, f"b12 {triple}")
+
+
+def test_layouts_coexist_in_one_pool_on_gpu():
+    """DP-written and TP-written blocks side by side in one pool, two calls (Sec. 5.2.3)."""
+    dp_t, tp_t = (LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)
+    geom = geometry(TINY)
+    dp, tp = oracle.View(geom, *dp_t), oracle.View(geom, *tp_t)
+    ctx_a, ctx_b = np.array([30, 70], dtype=np.int32), np.array([65, 5, 130], dtype=np.int32)
+    wa = wl.Workload("a", 11, 8, 2, 64, 16, 2, "x", ())
+    wb = wl.Workload("b", 12, 8, 2, 64, 16, 3, "x", ())
+    Ka, Va = wl.logical_kv(wa, ctx_a)
+    Kb, Vb = wl.logical_kv(wb, ctx_b)
+    qa, qb = wl.queries(wa), wl.queries(wb)
+    perm = torch.randperm(40, generator=wl.generator(11, wl.SUB_PERM)).numpy().astype(np.int32)
+    t_a, used = wl.assign_blocks(ctx_a, 16, perm)
+    t_b, _ = wl.assign_blocks(ctx_b, 32, perm[used:])
+    pool = wl.poisoned_pool(40, dp.query()["block_bytes"] // 2)
+    oracle.scatter(dp, pool, t_a, ctx_a, wl.seq_offsets(ctx_a), Ka, Va)
+    oracle.scatter(tp, pool, t_b, ctx_b, wl.seq_offsets(ctx_b), Kb, Vb)
+    dpool = dev_u16(pool)
+    qb_r = q_slice(qb, tp.query(), 1)
+    out_a = kv.paged_decode_attn(dev_u16(qa), dpool, torch.from_numpy(t_a).to(DEV),
+                                 torch.from_numpy(ctx_a).to(DEV), gpu_view(TINY, dp_t), 70)
+    out_b = kv.paged_decode_attn(dev_u16(qb_r), dpool, torch.from_numpy(t_b).to(DEV),
+                                 torch.from_numpy(ctx_b).to(DEV), gpu_view(TINY, tp_t), 130)
+    torch.cuda.synchronize()
+    check_close(bf16_bits_to_f64(out_a.cpu().numpy().view(np.uint16)),
+                oracle.paged_decode(dp, qa, pool, t_a, ctx_a), "dp part")
+    check_close(bf16_bits_to_f64(out_b.cpu().numpy().view(np.uint16)),
+                oracle.paged_decode(tp, qb_r, pool, t_b, ctx_b), "tp part")
+
+
+# ------------------------------------------------------------------------------------ repack
+
+def disjoint_tables(ctx, views, n_pool_blocks, index):
+    perm = torch.randperm(n_pool_blocks, generator=wl.generator(index, wl.SUB_PERM)).numpy().astype(np.int32)
+    tables, used = [], 0
+    for v in views:
+        t, k = wl.assign_blocks(ctx, v.query()["block_tokens"], perm[used:])
+        tables.append(t)
+        used += k
+    return tables
+
+
+def gpu_repack(dpool, w, src_t, dst_t, t_src, t_dst, ctx):
+    sv, dv = gpu_view(w, src_t), gpu_view(w, dst_t)
+    ts, td = torch.from_numpy(t_src).to(DEV), torch.from_numpy(t_dst).to(DEV)
+    n = torch.from_numpy(ctx).to(DEV)
+    n_blocks = dpool.numel() * 2 // sv.block_bytes
+    assert kv.kv_validate_tables(sv, n_blocks, ts, n, dv, td) == kv.KV_OK
+    kv.kv_repack(dpool, sv, dv, ts, td, n, int(ctx.max()))
+
+
+def test_tiny_repack_dp_tp2_dp_bit_exact():
+    """Tiny flow: DP -> TP2 r0 and r1 -> fresh DP blocks; after every step the whole pool must
+    equal the oracle's pool byte for byte; the round trip restores the DP blocks."""
+    geom = geometry(TINY)
+    dp_t, tp0_t, tp1_t = (LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 0), (LAYOUT_TP, 2, 1)
+    dp, tp0, tp1 = (oracle.View(geom, *t) for t in (dp_t, tp0_t, tp1_t))
+    ctx = wl.draw_ctx_lens(TINY)
+    K, V = wl.logical_kv(TINY, ctx)
+    off = wl.seq_offsets(ctx)
+    t_dp, t_tp0, t_tp1, t_back = disjoint_tables(ctx, [dp, tp0, tp1, dp], 128, 0)
+    pool = wl.poisoned_pool(128, dp.query()["block_bytes"] // 2)
+    oracle.scatter(dp, pool, t_dp, ctx, off, K, V)
+    dpool = dev_u16(pool)
+    steps = [(dp_t, tp0_t, t_dp, t_tp0, dp, tp0), (dp_t, tp1_t, t_dp, t_tp1, dp, tp1),
+             (tp0_t, dp_t, t_tp0, t_back, tp0, dp), (tp1_t, dp_t, t_tp1, t_back, tp1, dp)]
+    for src_t, dst_t, ts, td, sv, dv in steps:
+        gpu_repack(dpool, TINY, src_t, dst_t, ts, td, ctx)
+        oracle.repack(sv, dv, pool, ts, td, ctx)
+        torch.cuda.synchronize()
+        assert np.array_equal(dpool.cpu().numpy().view(np.uint16), pool), (src_t, dst_t)
+    got = dpool.cpu().numpy().view(np.uint16)
+    for s in range(len(ctx)):
+        nb = int(wl.blocks_needed(ctx[s:s + 1], 16)[0])
+        assert np.array_equal(got[t_back[s, :nb]], got[t_dp[s, :nb]])
+    # and attention through the TP views of the repacked blocks matches the oracle
+    q_full = wl.queries(TINY)
+    for r, (triple, view, table) in enumerate([(tp0_t, tp0, t_tp0), (tp1_t, tp1, t_tp1)]):
+        qr = q_slice(q_full, view.query(), r)
+        out = kv.paged_decode_attn(dev_u16(qr), dpool, torch.from_numpy(table).to(DEV),
+                                   torch.from_numpy(ctx).to(DEV), gpu_view(TINY, triple), 300)
+        torch.cuda.synchronize()
+        check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)),
+                    oracle.paged_decode(view, qr, pool, table, ctx), f"after repack r{r}")
+
+
+@pytest.mark.parametrize("hkv,d,b0,src_t,dst_t", [
+    (8, 128, 16, (LAYOUT_DP, 1, 0), (LAYOUT_TP, 4, 0)),
+    (8, 128, 16, (LAYOUT_TP, 4, 2), (LAYOUT_DP, 1, 0)),
+    (8, 128, 16, (LAYOUT_TP, 2, 1), (LAYOUT_TP, 8, 6)),
+    (8, 128, 16, (LAYOUT_DP, 8, 3), (LAYOUT_TP, 8, 3)),       # strided in-place slice -> compact
+    (6, 64, 12, (LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)),        # 3 common heads: run not a power of two
+    (8, 128, 16, (LAYOUT_TP, 2, 0), (LAYOUT_TP, 4, 3)),       # nothing in common: pool unchanged
+])
+def test_repack_bit_exact_various_views(hkv, d, b0, src_t, dst_t):
+    w = wl.Workload("rp", 40 + hkv, 4 * hkv, hkv, d, b0, 7, "x", ())
+    geom = geometry(w)
+    sv, dv = oracle.View(geom, *src_t), oracle.View(geom, *dst_t)
+    ctx = np.array([0, 1, b0, b0 + 1, 700, 1025, 64], dtype=np.int32)
+    K, V = wl.logical_kv(w, ctx)
+    t_src, t_dst = disjoint_tables(ctx, [sv, dv], 400, w.index)
+    pool = wl.poisoned_pool(400, sv.query()["block_bytes"] // 2)
+    oracle.scatter(sv, pool, t_src, ctx, wl.seq_offsets(ctx), K, V)
+    dpool = dev_u16(pool)
+    gpu_repack(dpool, w, src_t, dst_t, t_src, t_dst, ctx)
+    oracle.repack(sv, dv, pool, t_src, t_dst, ctx)
+    torch.cuda.synchronize()
+    assert np.array_equal(dpool.cpu().numpy().view(np.uint16), pool)
+
+
+def test_append_then_decode_matches_oracle():
+    """kv_append writes token n of every sequence through the view; the pool must equal the
+    oracle's scatter of n+1 tokens, and a decode over n+1 tokens must match."""
+    w = wl.Workload("ap", 50, 32, 8, 128, 16, 5, "x", ())
+    ctx1 = np.array([1, 16, 17, 129, 640], dtype=np.int32)       # lengths after the append
+    for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 4, 1), (LAYOUT_DP, 2, 1)]:
+        c = make_case(w, triple, ctx1)                            # pool holds all ctx1 tokens
+        ov, info = c.view, c.info
+        # start from a pool holding only the first ctx1 - 1 tokens
+        pool0 = wl.poisoned_pool(c.pool.shape[0], c.pool.shape[1])
+        oracle.scatter(ov, pool0, c.table, ctx1 - 1, c.seq_off, c.K, c.V)
+        h0, hl = info["kv_head0"], info["n_kv_local"]
+        last = c.seq_off[1:] - 1
+        k_new = np.ascontiguousarray(c.K[last][:, h0:h0 + hl])
+        v_new = np.ascontiguousarray(c.V[last][:, h0:h0 + hl])
+        dpool = dev_u16(pool0)
+        view = gpu_view(w, triple)
+        table = torch.from_numpy(c.table).to(DEV)
+        kv.kv_append(dpool, view, dev_u16(k_new), dev_u16(v_new), table,
+                     torch.from_numpy((ctx1 - 1).astype(np.int32)).to(DEV))
+        torch.cuda.synchronize()
+        assert np.array_equal(dpool.cpu().numpy().view(np.uint16), c.pool), triple
+        out = kv.paged_decode_attn(dev_u16(c.q), dpool, table, torch.from_numpy(ctx1).to(DEV), view, 640)
+        torch.cuda.synchronize()
+        check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)),
+                    oracle.paged_decode(ov, c.q, c.pool, c.table, ctx1), f"append {triple}")
+
+
+def test_validate_tables_reports_bad_contents():
+    view = gpu_view(TINY, (LAYOUT_DP, 1, 0))
+    n = torch.tensor([40, 20], dtype=torch.int32, device=DEV)
+    good = torch.tensor([[3, 1, 2], [0, 5, -1]], dtype=torch.int32, device=DEV)
+    assert kv.kv_validate_tables(view, 8, good, n) == kv.KV_OK
+    assert kv.kv_validate_tables(view, 4, good, n) == kv.KV_ERR_RANGE          # id 5 >= 4 blocks
+    dup = torch.tensor([[3, 1, 2], [0, 1, -1]], dtype=torch.int32, device=DEV)
+    assert kv.kv_validate_tables(view, 8, dup, n) == kv.KV_ERR_ALIAS
+    neg = torch.tensor([[3, -1, 2], [0, 5, -1]], dtype=torch.int32, device=DEV)
+    assert kv.kv_validate_tables(view, 8, neg, n) == kv.KV_ERR_RANGE
+    other = torch.tensor([[6, 7, 4], [2, 8, -1]], dtype=torch.int32, device=DEV)   # shares block 2
+    assert kv.kv_validate_tables(view, 16, good, n, view, other) == kv.KV_ERR_ALIAS
+    apart = torch.tensor([[6, 7, 4], [9, 8, -1]], dtype=torch.int32, device=DEV)
+    assert kv.kv_validate_tables(view, 16, good, n, view, apart) == kv.KV_OK
