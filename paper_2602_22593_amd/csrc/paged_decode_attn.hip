@@ -7,7 +7,12 @@
 // byte is fetched from HBM once.  A sequence with one chunk is finished in place; otherwise
 // each chunk leaves an un-normalised partial (m, l, acc[d]) in the workspace and a second small
 // kernel merges them:  m = max m_k, l = sum l_k 2^(m_k - m), acc = sum acc_k 2^(m_k - m).
-// Scores are kept in base-2 units (q is pre-multiplied by scale * log2(e)).
+// Scores are kept in base-2 units (multiplied by scale * log2(e)).
+//
+// Two main kernels:
+//   decode_mfma_kernel  head_dim 128, G <= 16, block capacity a multiple of 16: QK^T and PV on
+//                       the matrix cores (16x16x32 bf16 MFMA), the query group padded to 16.
+//   decode_valu_kernel  any G in {1,2,4,8}, head_dim 64 or 128, any block capacity: vector ALU.
 #include <math.h>
 
 #include "kv_internal.h"
@@ -18,17 +23,21 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr float kNegInf = -INFINITY;
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
-// fp32 -> bf16, round to nearest even (inputs here are finite or zero).
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
     uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // keep NaN a NaN
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
     u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return u >> 16;
 }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)f32_to_bf16_bits(f); }
 
 __device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8])
 {
@@ -47,6 +56,7 @@ struct decode_args {
     const int32_t* ctx_lens;
     kv_view_dev v;
     float scale_log2e;
+    int32_t group;         // G = query heads per KV head
     int32_t chunk_tokens;
     int32_t max_chunks;
     float* part_acc;  // [batch][n_q_local][max_chunks][D]
@@ -65,6 +75,202 @@ __device__ __forceinline__ void combine(float& m, float& l, float (&a)[N], float
 #pragma unroll
     for (int e = 0; e < N; ++e) a[e] = a[e] * c1 + a2[e] * c2;
     m = mn;
+}
+
+// Workgroup epilogue shared by both main kernels: the kWaves per-wave results for G heads sit in
+// LDS (s_acc[w][g][e], s_ml[w][g][0..1]); combine them and write either the final bf16 row (the
+// sequence has a single chunk) or this chunk's partial.
+template <int D, int GMAX>
+__device__ __forceinline__ void finish_chunk(const decode_args& a, float (&s_acc)[kWaves][GMAX][D],
+                                             float (&s_ml)[kWaves][GMAX][2], int G, int s, int hl,
+                                             int chunk, int n_chunks)
+{
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int g = idx / D, e = idx - g * D;
+        float mm = kNegInf;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[w][g][0]);
+        const float ms = (mm == kNegInf) ? 0.f : mm;
+        float ll = 0.f, aa = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float cw = exp2f(s_ml[w][g][0] - ms);
+            ll += s_ml[w][g][1] * cw;
+            aa += s_acc[w][g][e] * cw;
+        }
+        const int qi = hl * G + g;
+        if (n_chunks <= 1) {
+            const float o = ll > 0.f ? aa / ll : 0.f;
+            a.out[((int64_t)s * a.v.n_q_local + qi) * D + e] = f32_to_bf16(o);
+        } else {
+            const int64_t rec = ((int64_t)s * a.v.n_q_local + qi) * a.max_chunks + chunk;
+            a.part_acc[rec * D + e] = aa;
+            if (e == 0) {
+                a.part_ml[rec * 2 + 0] = mm;
+                a.part_ml[rec * 2 + 1] = ll;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core kernel (head_dim 128).  One wavefront walks tiles of 32 tokens of its chunk.
+//
+// Lane l = (r = l % 16, quad = l / 16).  Both products put the KV data in the MFMA A operand
+// (row index = r) and the query group in the B operand (column index = r = query head g):
+//   S^T[token][g] = K[token][:] . Q[g][:]     A = K rows: lane (r, quad) holds the 8 elements
+//                                              [32 kk + 8 quad, +8) of row r, kk = 0..3
+//   O^T[e][g]     = sum_t V[t][e] P[g][t]     A = V^T, B = P^T; contraction over the 32 tokens
+// The C layout of S^T (lane (g, quad) holds tokens 4 quad + i of a 16-row half) is, element for
+// element, the B layout the PV product needs if the contraction index k = 8 quad + 4 h + i stands
+// for token 16 h + 4 i + quad; so row r of half h of the K operand is token 16 h + 4 (r % 4) + r / 4,
+// and V is loaded row-wise (lane (c = r, quad) reads the 16 bytes [8c, 8c+8) of tokens
+// 4 i' + quad, i' = 0..7) and transposed inside the lane with byte permutes.  No data crosses
+// lanes except the running maximum.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 as_bf16x8(kv_u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(decode_args a)
+{
+    constexpr int D = 128;
+    const int chunk = blockIdx.x, hl = blockIdx.y, s = blockIdx.z;
+    const int n = a.ctx_lens[s];
+    const int cs = chunk * a.chunk_tokens;
+    if (cs >= n && chunk != 0) return;
+    const int ce = min(n, cs + a.chunk_tokens);
+    const int n_chunks = (n + a.chunk_tokens - 1) / a.chunk_tokens;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, quad = lane >> 4;
+    const int G = a.group;
+    const kv_view_dev& v = a.v;
+    const int32_t* trow = a.table + (int64_t)s * a.table_stride;
+
+    // B operand of the score product: lane (g = r, quad) holds q[g][32 kk + 8 quad, +8)
+    bf16x8 qb[4];
+    {
+        const uint16_t* qrow = a.q + ((int64_t)s * v.n_q_local + hl * G + min(r, G - 1)) * D;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            kv_u32x4 raw = *reinterpret_cast<const kv_u32x4*>(qrow + kk * 32 + quad * 8);
+            if (r >= G) raw = kv_u32x4{0u, 0u, 0u, 0u};
+            qb[kk] = as_bf16x8(raw);
+        }
+    }
+
+    float m_run = kNegInf, l_run = 0.f;
+    f32x4 oacc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) oacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t* kplane = a.pool + v.head_off + hl * D;
+    const int k_row = 4 * (r & 3) + (r >> 2);  // token (within a 16-token half) held in A row r
+
+    for (int t0 = cs + 32 * wave; t0 < ce; t0 += 32 * kWaves) {
+        // the two 16-token halves of the tile each lie inside one block (capacity % 16 == 0)
+        const uint16_t* hbase[2];
+        int hstart[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int ts = min(t0 + 16 * h, ce - 1);
+            int bj, slot;
+            kv_split_token(v, ts, bj, slot);
+            hstart[h] = ts - slot;  // first token of that block
+            hbase[h] = kplane + (int64_t)trow[bj] * v.block_elems;
+        }
+        kv_u32x4 kA[2][4], vN[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int tok = min(t0 + 16 * h + k_row, ce - 1);
+            const uint16_t* p = hbase[h] + (tok - hstart[h]) * v.token_stride + quad * 8;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kA[h][kk] = *reinterpret_cast<const kv_u32x4*>(p + kk * 32);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int h = i >> 2;
+            const int tok = min(t0 + 4 * i + quad, ce - 1);
+            const uint16_t* p = hbase[h] + v.plane_elems + (tok - hstart[h]) * v.token_stride + r * 8;
+            vN[i] = *reinterpret_cast<const kv_u32x4*>(p);
+        }
+
+        // scores
+        f32x4 sacc[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            sacc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                sacc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[h][kk]), qb[kk], sacc[h], 0, 0, 0);
+        }
+        float sv[8];
+        float mx = kNegInf;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tok = t0 + 16 * h + 4 * i + quad;
+                const float x = tok < ce ? sacc[h][i] * a.scale_log2e : kNegInf;
+                sv[4 * h + i] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one valid token
+        const float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        uint32_t pw[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t b0 = f32_to_bf16_bits(exp2f(sv[2 * u] - m_new));
+            const uint32_t b1 = f32_to_bf16_bits(exp2f(sv[2 * u + 1] - m_new));
+            psum += __uint_as_float(b0 << 16) + __uint_as_float(b1 << 16);
+            pw[u] = b0 | (b1 << 16);
+        }
+        l_run = l_run * alpha + psum;
+        const bf16x8 pb = as_bf16x8(kv_u32x4{pw[0], pw[1], pw[2], pw[3]});
+#pragma unroll
+        for (int j = 0; j < 8; ++j) oacc[j] *= alpha;
+
+        // V^T operands: element j of the 8 loaded rows, packed token-pair-wise
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            kv_u32x4 lo, hi;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                lo[u] = __builtin_amdgcn_perm(vN[2 * u + 1][w], vN[2 * u][w], 0x05040100u);
+                hi[u] = __builtin_amdgcn_perm(vN[2 * u + 1][w], vN[2 * u][w], 0x07060302u);
+            }
+            oacc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(lo), pb, oacc[2 * w], 0, 0, 0);
+            oacc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(hi), pb, oacc[2 * w + 1], 0, 0, 0);
+        }
+    }
+
+    // per-lane partial sums of l over the 4 quads
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+
+    // lane (g = r, quad) holds O[g][32 quad + 8 i + j] in oacc[j][i]
+    __shared__ float s_acc[kWaves][16][D];
+    __shared__ float s_ml[kWaves][16][2];
+    if (r < G) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float4 lo4 = make_float4(oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]);
+            float4 hi4 = make_float4(oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]);
+            float* dst = &s_acc[wave][r][32 * quad + 8 * i];
+            *reinterpret_cast<float4*>(dst) = lo4;
+            *reinterpret_cast<float4*>(dst + 4) = hi4;
+        }
+        if (quad == 0) {
+            s_ml[wave][r][0] = m_run;
+            s_ml[wave][r][1] = l_run;
+        }
+    }
+    __syncthreads();
+    finish_chunk<D, 16>(a, s_acc, s_ml, G, s, hl, chunk, n_chunks);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -200,53 +406,58 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(decode_args a)
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-        const int g = idx / D, e = idx - g * D;
-        float mm = kNegInf;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, s_ml[w][g][0]);
-        const float ms = (mm == kNegInf) ? 0.f : mm;
-        float ll = 0.f, aa = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float cw = exp2f(s_ml[w][g][0] - ms);
-            ll += s_ml[w][g][1] * cw;
-            aa += s_acc[w][g][e] * cw;
-        }
-        const int qi = hl * G + g;
-        if (n_chunks <= 1) {
-            const float o = ll > 0.f ? aa / ll : 0.f;
-            a.out[((int64_t)s * v.n_q_local + qi) * D + e] = f32_to_bf16(o);
-        } else {
-            const int64_t rec = ((int64_t)s * v.n_q_local + qi) * a.max_chunks + chunk;
-            a.part_acc[rec * D + e] = aa;
-            if (e == 0) {
-                a.part_ml[rec * 2 + 0] = mm;
-                a.part_ml[rec * 2 + 1] = ll;
-            }
-        }
-    }
+    finish_chunk<D, G>(a, s_acc, s_ml, G, s, hl, chunk, n_chunks);
 }
 
-// Merge the partials of one (sequence, local query head); one thread per output element.
+// ---------------------------------------------------------------------------------------------
+// Merge the partials of one (sequence, local query head).  256 lanes = 32 column groups of
+// D/32 elements x 8 slices of the chunk list; maxima first, then one weighted pass.
+// ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(decode_args a)
+__global__ __launch_bounds__(256) void decode_merge_kernel(decode_args a)
 {
-    const int qi = blockIdx.x, s = blockIdx.y, e = threadIdx.x;
+    constexpr int EPT = D / 32;  // elements per lane
+    const int qi = blockIdx.x, s = blockIdx.y;
     const int n = a.ctx_lens[s];
     const int n_chunks = (n + a.chunk_tokens - 1) / a.chunk_tokens;
     if (n_chunks <= 1) return;  // finished in place by the main kernel
+    const int tid = threadIdx.x, cg = tid & 31, slice = tid >> 5;
     const int64_t rec0 = ((int64_t)s * a.v.n_q_local + qi) * a.max_chunks;
+
+    __shared__ float s_red[8][D];
+    __shared__ float s_l[8];
+    __shared__ float s_max[4];
     float mm = kNegInf;
-    for (int k = 0; k < n_chunks; ++k) mm = fmaxf(mm, a.part_ml[(rec0 + k) * 2]);
-    float ll = 0.f, aa = 0.f;
-#pragma unroll 4
-    for (int k = 0; k < n_chunks; ++k) {
+    for (int k = tid; k < n_chunks; k += 256) mm = fmaxf(mm, a.part_ml[(rec0 + k) * 2]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off));
+    if ((tid & 63) == 0) s_max[tid >> 6] = mm;
+    __syncthreads();
+    mm = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+
+    float ll = 0.f, acc[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
+    for (int k = slice; k < n_chunks; k += 8) {
         const float cw = exp2f(a.part_ml[(rec0 + k) * 2] - mm);
         ll += a.part_ml[(rec0 + k) * 2 + 1] * cw;
-        aa += a.part_acc[(rec0 + k) * D + e] * cw;
+        const float* src = a.part_acc + (rec0 + k) * D + cg * EPT;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) acc[e] += src[e] * cw;
     }
-    a.out[((int64_t)s * a.v.n_q_local + qi) * D + e] = f32_to_bf16(aa / ll);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) s_red[slice][cg * EPT + e] = acc[e];
+    if (cg == 0) s_l[slice] = ll;
+    __syncthreads();
+    if (tid < D) {
+        float tot = 0.f, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            tot += s_red[w][tid];
+            lt += s_l[w];
+        }
+        a.out[((int64_t)s * a.v.n_q_local + qi) * D + tid] = f32_to_bf16(tot / lt);
+    }
 }
 
 int pick_chunk_tokens(const kv_view* v, int batch, int max_ctx_len)
@@ -260,23 +471,34 @@ int pick_chunk_tokens(const kv_view* v, int batch, int max_ctx_len)
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 template <int D, int G>
-void launch_valu(const decode_args& a, int max_chunks, int n_kv_local, int batch, hipStream_t st)
+void launch_valu(const decode_args& a, dim3 grid, hipStream_t st)
 {
-    dim3 grid((unsigned)max_chunks, (unsigned)n_kv_local, (unsigned)batch);
     hipLaunchKernelGGL((decode_valu_kernel<D, G>), grid, dim3(kThreads), 0, st, a);
 }
 
 template <int D>
-int launch_for_group(const decode_args& a, int G, int max_chunks, int n_kv_local, int batch,
-                     hipStream_t st)
+int launch_valu_for_group(const decode_args& a, dim3 grid, hipStream_t st)
 {
-    switch (G) {
-        case 1: launch_valu<D, 1>(a, max_chunks, n_kv_local, batch, st); return KV_OK;
-        case 2: launch_valu<D, 2>(a, max_chunks, n_kv_local, batch, st); return KV_OK;
-        case 4: launch_valu<D, 4>(a, max_chunks, n_kv_local, batch, st); return KV_OK;
-        case 8: launch_valu<D, 8>(a, max_chunks, n_kv_local, batch, st); return KV_OK;
+    switch (a.group) {
+        case 1: launch_valu<D, 1>(a, grid, st); return KV_OK;
+        case 2: launch_valu<D, 2>(a, grid, st); return KV_OK;
+        case 4: launch_valu<D, 4>(a, grid, st); return KV_OK;
+        case 8: launch_valu<D, 8>(a, grid, st); return KV_OK;
         default: return KV_ERR_UNSUPPORTED;
     }
+}
+
+// Which main kernel serves a view: 1 = matrix-core kernel, 2 = vector-ALU kernel, 0 = none.
+int pick_kernel(const kv_view* view)
+{
+    const int D = view->geom.head_dim, G = view->group;
+    const bool mfma_ok = D == 128 && G <= 16 && view->block_tokens % 16 == 0;
+    const bool valu_ok = (D == 64 || D == 128) && (G == 1 || G == 2 || G == 4 || G == 8);
+    const int64_t forced = kv_option_force_kernel();
+    if (forced == 1) return mfma_ok ? 1 : 0;
+    if (forced == 2) return valu_ok ? 2 : 0;
+    if (mfma_ok) return 1;
+    return valu_ok ? 2 : 0;
 }
 
 }  // namespace
@@ -305,9 +527,9 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     if (max_ctx_len > 0 && (!kv_pool || !block_table)) return KV_ERR_INVALID_ARG;
     const int64_t need_cols = ((int64_t)max_ctx_len + view->block_tokens - 1) / view->block_tokens;
     if (block_table_stride < need_cols) return KV_ERR_INVALID_ARG;
-    const int D = view->geom.head_dim, G = view->group;
-    if (D != 64 && D != 128) return KV_ERR_UNSUPPORTED;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return KV_ERR_UNSUPPORTED;
+    const int D = view->geom.head_dim;
+    const int kernel = pick_kernel(view);
+    if (kernel == 0) return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || view->n_kv_local > 65535) return KV_ERR_UNSUPPORTED;
 
     const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
@@ -330,6 +552,7 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     a.v = kv_view_to_dev(view);
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     a.scale_log2e = sc * 1.4426950408889634f;
+    a.group = view->group;
     a.chunk_tokens = chunk;
     a.max_chunks = (int32_t)max_chunks;
     const int64_t recs = (int64_t)batch * view->n_q_local * max_chunks;
@@ -339,20 +562,24 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
                     : nullptr;
 
     hipStream_t st = (hipStream_t)hip_stream;
+    const dim3 grid((unsigned)max_chunks, (unsigned)view->n_kv_local, (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
-    int rc = (D == 128) ? launch_for_group<128>(a, G, (int)max_chunks, view->n_kv_local, batch, st)
-                        : launch_for_group<64>(a, G, (int)max_chunks, view->n_kv_local, batch, st);
+    int rc = KV_OK;
+    if (kernel == 1)
+        hipLaunchKernelGGL(decode_mfma_kernel, grid, dim3(kThreads), 0, st, a);
+    else
+        rc = (D == 128) ? launch_valu_for_group<128>(a, grid, st) : launch_valu_for_group<64>(a, grid, st);
     if (rc) return rc;
     kv_prof_end(KV_PROF_DECODE_MAIN, slot, st);
     rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn launch");
     if (rc) return rc;
     if (max_chunks > 1) {
         slot = kv_prof_begin(KV_PROF_DECODE_MERGE, st);
-        dim3 grid((unsigned)view->n_q_local, (unsigned)batch);
+        dim3 mgrid((unsigned)view->n_q_local, (unsigned)batch);
         if (D == 128)
-            hipLaunchKernelGGL(decode_merge_kernel<128>, grid, dim3(128), 0, st, a);
+            hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(256), 0, st, a);
         else
-            hipLaunchKernelGGL(decode_merge_kernel<64>, grid, dim3(64), 0, st, a);
+            hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(256), 0, st, a);
         kv_prof_end(KV_PROF_DECODE_MERGE, slot, st);
         rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn merge launch");
     }

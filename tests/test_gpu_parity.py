@@ -25,6 +25,7 @@ def require_gpu_and_library():
     kv.lib()  # raises if the HIP library is not built: there is no fallback
     yield
     kv.kv_set_option("chunk_tokens", 0)
+    kv.kv_set_option("force_kernel", 0)
 
 
 def dev_u16(a: np.ndarray) -> torch.Tensor:
@@ -66,21 +67,24 @@ def test_tiny_config_all_views(triple, chunk):
 RAGGED = np.array([1, 15, 16, 17, 0, 511, 513, 1300, 2049, 64], dtype=np.int32)
 
 
+@pytest.mark.parametrize("kernel", [0, 2])      # 0 = automatic (matrix-core kernel at d = 128), 2 = vector-ALU kernel
 @pytest.mark.parametrize("chunk", [0, 256])
 @pytest.mark.parametrize("hq,hkv,triple", [
     (32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 2, 1)), (32, 8, (LAYOUT_TP, 4, 3)),
     (32, 8, (LAYOUT_TP, 8, 5)), (32, 8, (LAYOUT_DP, 4, 2)), (64, 8, (LAYOUT_TP, 8, 7)),
     (64, 8, (LAYOUT_DP, 1, 0)), (16, 8, (LAYOUT_TP, 2, 0)), (8, 8, (LAYOUT_TP, 4, 1)),
 ])
-def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk):
+def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk, kernel):
     """Head dim 128 at the Llama shapes (G = 4, 8) and smaller groups (G = 2, 1): lengths that
     span several tiles, end mid-block, are empty, or are exactly one block."""
     kv.kv_set_option("chunk_tokens", chunk)
+    kv.kv_set_option("force_kernel", kernel)
     w = wl.Workload("ragged", 20 + hq // 8, hq, hkv, 128, 16, len(RAGGED), "x", ())
     c = make_case(w, triple, RAGGED)
     want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
     got = run_gpu_decode(c, gpu_view(w, triple))
-    check_close(got, want, f"{hq}/{hkv} {triple} chunk {chunk}")
+    kv.kv_set_option("force_kernel", 0)
+    check_close(got, want, f"{hq}/{hkv} {triple} chunk {chunk} kernel {kernel}")
     assert (got[4] == 0).all()                       # ctx_len 0 -> zeros
     # ctx_len 1 -> the V row itself, exactly (bf16 in, bf16 out)
     G = hq // hkv
