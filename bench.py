@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="independent pools cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip repack and the other workloads")
+    ap.add_argument("--probe", action="store_true",
+                    help="only run the known-traffic streaming kernels (read 1 GiB, copy 1 GiB) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -75,6 +77,20 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+
+    def stream_ceiling(n_bytes=1 << 30, iters=10):
+        """Measured read and copy rates of the trivial streaming kernels (GB/s)."""
+        src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty(n_bytes, dtype=torch.uint8, device="cuda")
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        rd = harness.time_calls(lambda i: kv.kv_probe_read(src, n_cu), iters, 3)
+        cp = harness.time_calls(lambda i: kv.kv_probe_copy(dst, src, n_cu), iters, 3)
+        return {"read_GBps": round(n_bytes / rd / 1e6, 1), "copy_read_plus_write_GBps": round(2 * n_bytes / cp / 1e6, 1),
+                "bytes": n_bytes, "workgroups": n_cu}
+
+    if args.probe:
+        print(json.dumps({"probe": stream_ceiling()}))
+        return
     w = wl.WORKLOADS[args.workload]
     triple = tuple(int(x) for x in args.view.split(",")) if args.view else w.views[0]
 
@@ -132,6 +148,7 @@ def main():
                      "merge_kernel_us": round(merge_ms / max(n_merge, 1) * 1e3, 2),
                      "algorithmic_bytes_per_launch": case.kv_bytes},
     }
+    result["roofline"]["measured_stream_ceiling"] = stream_ceiling()
 
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(case)

@@ -81,7 +81,29 @@ int kv_record_hip_error(hipError_t e, const char* what);
 // Library-wide tunables (kv_set_option).
 int64_t kv_option_chunk_tokens();
 int64_t kv_option_force_kernel();
+int64_t kv_option_waves_per_cu();
+int64_t kv_option_variant();
 
 // Per-kernel event brackets for kv_profile_*: begin returns a slot (or -1 when disabled).
 int kv_prof_begin(int which, hipStream_t st);
 void kv_prof_end(int which, int slot, hipStream_t st);
+
+// ---- matrix-core decode kernel with an even split over resident wavefronts --------------------
+#define KV_STREAMK_MAX_BATCH 2048
+struct kv_streamk_args {
+    const uint16_t* q;
+    uint16_t* out;
+    const uint16_t* pool;
+    const int32_t* table;
+    int64_t table_stride;
+    const int32_t* ctx_lens;
+    kv_view_dev v;
+    float scale_log2e;
+    int32_t group;     // query heads per KV head
+    int32_t batch;
+    int32_t n_waves;   // wavefronts launched (multiple of 4)
+    float* part_acc;   // [n_waves + batch * n_kv_local][group][128]
+    float* part_ml;    // [n_waves + batch * n_kv_local][group][2]
+};
+size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
+int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

@@ -21,9 +21,13 @@ int kv_record_hip_error(hipError_t e, const char* what)
 
 static std::atomic<int64_t> g_chunk_tokens{0};
 static std::atomic<int64_t> g_force_kernel{0};
+static std::atomic<int64_t> g_waves_per_cu{0};
+static std::atomic<int64_t> g_variant{0};
 
 int64_t kv_option_chunk_tokens() { return g_chunk_tokens.load(); }
 int64_t kv_option_force_kernel() { return g_force_kernel.load(); }
+int64_t kv_option_waves_per_cu() { return g_waves_per_cu.load(); }
+int64_t kv_option_variant() { return g_variant.load(); }
 
 // ---- per-kernel event brackets -----------------------------------------------------------
 namespace {
@@ -172,6 +176,16 @@ int kv_set_option(const char* key, int64_t value)
         g_force_kernel.store(value);
         return KV_OK;
     }
+    if (!strcmp(key, "variant")) {
+        if (value < 0 || value > 255) return KV_ERR_INVALID_ARG;
+        g_variant.store(value);
+        return KV_OK;
+    }
+    if (!strcmp(key, "waves_per_cu")) {
+        if (value < 0 || value > 32 || (value % 4) != 0) return KV_ERR_INVALID_ARG;
+        g_waves_per_cu.store(value);
+        return KV_OK;
+    }
     return KV_ERR_INVALID_ARG;
 }
 
@@ -180,6 +194,8 @@ int64_t kv_get_option(const char* key)
     if (!key) return -1;
     if (!strcmp(key, "chunk_tokens")) return g_chunk_tokens.load();
     if (!strcmp(key, "force_kernel")) return g_force_kernel.load();
+    if (!strcmp(key, "waves_per_cu")) return g_waves_per_cu.load();
+    if (!strcmp(key, "variant")) return g_variant.load();
     return -1;
 }
 

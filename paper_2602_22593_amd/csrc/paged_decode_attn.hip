@@ -488,17 +488,47 @@ int launch_valu_for_group(const decode_args& a, dim3 grid, hipStream_t st)
     }
 }
 
-// Which main kernel serves a view: 1 = matrix-core kernel, 2 = vector-ALU kernel, 0 = none.
-int pick_kernel(const kv_view* view)
+// Which main kernel serves a call: 1 = matrix-core kernel with the even split over resident
+// wavefronts, 2 = vector-ALU kernel (chunked), 3 = matrix-core kernel (chunked), 0 = none.
+int pick_kernel(const kv_view* view, int batch)
 {
     const int D = view->geom.head_dim, G = view->group;
     const bool mfma_ok = D == 128 && G <= 16 && view->block_tokens % 16 == 0;
+    const bool streamk_ok = mfma_ok && batch <= KV_STREAMK_MAX_BATCH;
     const bool valu_ok = (D == 64 || D == 128) && (G == 1 || G == 2 || G == 4 || G == 8);
     const int64_t forced = kv_option_force_kernel();
-    if (forced == 1) return mfma_ok ? 1 : 0;
+    if (forced == 1) return streamk_ok ? 1 : 0;
     if (forced == 2) return valu_ok ? 2 : 0;
-    if (mfma_ok) return 1;
+    if (forced == 3) return mfma_ok ? 3 : 0;
+    if (streamk_ok) return 1;
+    if (mfma_ok) return 3;
     return valu_ok ? 2 : 0;
+}
+
+// Wavefronts the even-split kernel launches: all resident at once, one per SIMD by default
+// (fewer, fatter streams measured faster than more, thinner ones).
+int streamk_waves()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    int64_t per_cu = kv_option_waves_per_cu();
+    if (per_cu <= 0) per_cu = 4;
+    return (int)(cus * per_cu);
+}
+
+size_t chunked_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
+{
+    const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
+    const int64_t max_chunks = ((int64_t)max_ctx_len + chunk - 1) / chunk;
+    if (max_chunks <= 1) return 256;
+    const int64_t recs = (int64_t)batch * view->n_q_local * max_chunks;
+    return align_up((size_t)recs * view->geom.head_dim * 4, 256) + align_up((size_t)recs * 2 * 4, 256);
 }
 
 }  // namespace
@@ -506,11 +536,9 @@ int pick_kernel(const kv_view* view)
 extern "C" size_t paged_decode_attn_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
 {
     if (!kv_view_ok(view) || batch <= 0 || max_ctx_len <= 0) return 256;
-    const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
-    const int64_t max_chunks = ((int64_t)max_ctx_len + chunk - 1) / chunk;
-    if (max_chunks <= 1) return 256;
-    const int64_t recs = (int64_t)batch * view->n_q_local * max_chunks;
-    return align_up((size_t)recs * view->geom.head_dim * 4, 256) + align_up((size_t)recs * 2 * 4, 256);
+    const int kernel = pick_kernel(view, batch);
+    if (kernel == 1) return kv_streamk_workspace_bytes(view, batch, streamk_waves());
+    return chunked_workspace_bytes(view, batch, max_ctx_len);
 }
 
 extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
@@ -528,14 +556,42 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     const int64_t need_cols = ((int64_t)max_ctx_len + view->block_tokens - 1) / view->block_tokens;
     if (block_table_stride < need_cols) return KV_ERR_INVALID_ARG;
     const int D = view->geom.head_dim;
-    const int kernel = pick_kernel(view);
+    const int kernel = pick_kernel(view, batch);
     if (kernel == 0) return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || view->n_kv_local > 65535) return KV_ERR_UNSUPPORTED;
+    const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    if (kernel == 1 && max_ctx_len > 0) {
+        // tiles of 32 tokens over all (sequence, head) pairs must fit 31 bits
+        if (((int64_t)max_ctx_len / 32 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
+            return KV_ERR_UNSUPPORTED;
+        const int n_waves = streamk_waves();
+        const size_t need_sk = kv_streamk_workspace_bytes(view, batch, n_waves);
+        if (!workspace) return KV_ERR_INVALID_ARG;
+        if (workspace_bytes < need_sk) return KV_ERR_WORKSPACE;
+        if (((uintptr_t)workspace & 255u) != 0) return KV_ERR_INVALID_ARG;
+        kv_streamk_args k;
+        k.q = (const uint16_t*)q;
+        k.out = (uint16_t*)out;
+        k.pool = (const uint16_t*)kv_pool;
+        k.table = block_table;
+        k.table_stride = block_table_stride;
+        k.ctx_lens = ctx_lens;
+        k.v = kv_view_to_dev(view);
+        k.scale_log2e = sc * 1.4426950408889634f;
+        k.group = view->group;
+        k.batch = batch;
+        k.n_waves = n_waves;
+        k.part_acc = nullptr;
+        k.part_ml = nullptr;
+        return kv_streamk_launch(k, view, workspace, st);
+    }
 
     const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
     int64_t max_chunks = ((int64_t)max_ctx_len + chunk - 1) / chunk;
     if (max_chunks < 1) max_chunks = 1;
-    const size_t need = paged_decode_attn_workspace_bytes(view, batch, max_ctx_len);
+    const size_t need = chunked_workspace_bytes(view, batch, max_ctx_len);
     if (max_chunks > 1) {
         if (!workspace) return KV_ERR_INVALID_ARG;
         if (workspace_bytes < need) return KV_ERR_WORKSPACE;
@@ -550,7 +606,6 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     a.table_stride = block_table_stride;
     a.ctx_lens = ctx_lens;
     a.v = kv_view_to_dev(view);
-    const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     a.scale_log2e = sc * 1.4426950408889634f;
     a.group = view->group;
     a.chunk_tokens = chunk;
@@ -561,11 +616,10 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
                     ? (float*)((char*)workspace + align_up((size_t)recs * D * 4, 256))
                     : nullptr;
 
-    hipStream_t st = (hipStream_t)hip_stream;
     const dim3 grid((unsigned)max_chunks, (unsigned)view->n_kv_local, (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     int rc = KV_OK;
-    if (kernel == 1)
+    if (kernel == 3 || kernel == 1)
         hipLaunchKernelGGL(decode_mfma_kernel, grid, dim3(kThreads), 0, st, a);
     else
         rc = (D == 128) ? launch_valu_for_group<128>(a, grid, st) : launch_valu_for_group<64>(a, grid, st);

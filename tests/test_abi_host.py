@@ -141,7 +141,7 @@ def test_unsupported_shapes_are_reported():
     v = kv.kv_view_create(32, 8, 256, 16, kv.KV_LAYOUT_DP, 1, 0)       # head_dim 256: no kernel
     assert L.paged_decode_attn(fake, fake, fake, 10, fake, 8, fake, 1, 16, v.handle, 0.0, fake, 1 << 20,
                                None) == kv.KV_ERR_UNSUPPORTED
-    v = kv.kv_view_create(48, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)       # group of 6
+    v = kv.kv_view_create(8 * 24, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)   # group of 24: above the MFMA tile, not a VALU size
     assert L.paged_decode_attn(fake, fake, fake, 10, fake, 8, fake, 1, 16, v.handle, 0.0, fake, 1 << 20,
                                None) == kv.KV_ERR_UNSUPPORTED
 

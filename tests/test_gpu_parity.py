@@ -67,7 +67,7 @@ def test_tiny_config_all_views(triple, chunk):
 RAGGED = np.array([1, 15, 16, 17, 0, 511, 513, 1300, 2049, 64], dtype=np.int32)
 
 
-@pytest.mark.parametrize("kernel", [0, 2])      # 0 = automatic (matrix-core kernel at d = 128), 2 = vector-ALU kernel
+@pytest.mark.parametrize("kernel", [0, 2, 3])   # 0 = automatic (even-split matrix-core kernel at d = 128), 2 = vector-ALU, 3 = chunked matrix-core
 @pytest.mark.parametrize("chunk", [0, 256])
 @pytest.mark.parametrize("hq,hkv,triple", [
     (32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 2, 1)), (32, 8, (LAYOUT_TP, 4, 3)),
@@ -91,6 +91,29 @@ def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk, kernel):
     for i in range(c.info["n_q_local"]):
         g = c.info["kv_head0"] + i // G
         assert np.array_equal(got[0, i], bf16_bits_to_f64(c.V[c.seq_off[0], g]))
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("wpc", [4, 12])
+def test_even_split_kernel_variants(variant, wpc):
+    """The even-split matrix-core kernel in its build variants (K fetched operand-wise or row-wise
+    through LDS; with or without register double buffering) and launch widths; lengths chosen so
+    that wavefront ranges cross sequence and head boundaries and single-piece pairs occur."""
+    kv.kv_set_option("variant", variant)
+    kv.kv_set_option("waves_per_cu", wpc)
+    try:
+        lens = np.array([1, 31, 32, 33, 0, 511, 513, 4100, 2049, 64, 7000, 96], dtype=np.int32)
+        for hq, hkv, triple in [(32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 4, 1)),
+                                (64, 8, (LAYOUT_TP, 8, 2)), (32, 8, (LAYOUT_DP, 2, 1))]:
+            w = wl.Workload("variants", 60 + hq // 8, hq, hkv, 128, 16, len(lens), "x", ())
+            c = make_case(w, triple, lens)
+            want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+            got = run_gpu_decode(c, gpu_view(w, triple))
+            check_close(got, want, f"variant {variant} wpc {wpc} {hq}/{hkv} {triple}")
+            assert (got[4] == 0).all()
+    finally:
+        kv.kv_set_option("variant", 0)
+        kv.kv_set_option("waves_per_cu", 0)
 
 
 def test_explicit_scale_and_large_logits():
