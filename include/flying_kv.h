@@ -208,6 +208,10 @@ int kv_profile_read(int which, double* total_ms, int64_t* n_launches);
  */
 int kv_probe_read(const void* src, size_t bytes, void* sink, int n_workgroups, void* hip_stream);
 int kv_probe_copy(void* dst, const void* src, size_t bytes, int n_workgroups, void* hip_stream);
+/* Same read, but of whole pool blocks in the order of block_ids (device, int32[n_ids]): the
+ * ceiling of a paged pool's access pattern, with no arithmetic on the data. */
+int kv_probe_read_blocks(const void* pool, const int32_t* block_ids, int n_ids, int64_t block_bytes,
+                         void* sink, int n_workgroups, void* hip_stream);
 
 const char* kv_strerror(int status);   /* static string, never null */
 const char* kv_last_hip_error(void);   /* text of the last HIP failure seen by this thread */

@@ -257,3 +257,14 @@ def kv_probe_copy(dst: torch.Tensor, src: torch.Tensor, n_workgroups: int, strea
     _check(lib().kv_probe_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                src.numel() * src.element_size(), n_workgroups, _stream_ptr(stream)),
            "kv_probe_copy")
+
+
+def kv_probe_read_blocks(pool: torch.Tensor, block_ids: torch.Tensor, block_bytes: int,
+                         n_workgroups: int, stream=None) -> None:
+    """Stream the pool blocks listed in ``block_ids`` (int32, device) once, block by block."""
+    L = lib()
+    L.kv_probe_read_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_int,
+                                       C.c_void_p]
+    _check(L.kv_probe_read_blocks(C.c_void_p(pool.data_ptr()), C.c_void_p(block_ids.data_ptr()),
+                                  int(block_ids.numel()), int(block_bytes), None, n_workgroups,
+                                  _stream_ptr(stream)), "kv_probe_read_blocks")

@@ -38,20 +38,22 @@ struct tile_regs {
 
 // K/V bytes are used once per call: fetch them with the streaming (non-temporal) policy so that
 // they do not displace each other in the cache hierarchy on their way through.
-__device__ __forceinline__ kv_u32x4 ld16(const uint16_t* base, uint32_t elem_off)
+// `base` is the same for the whole wavefront, `byte_off` a 32-bit per-lane offset: the form the
+// hardware addresses with a scalar base register pair plus one vector offset register.
+__device__ __forceinline__ kv_u32x4 ld16(const char* base, uint32_t byte_off)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(base + elem_off));
+    return __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(base + byte_off));
 }
-__device__ __forceinline__ kv_u32x4 ld16_cached(const uint16_t* base, uint32_t elem_off)
+__device__ __forceinline__ kv_u32x4 ld16_cached(const char* base, uint32_t byte_off)
 {
-    return *reinterpret_cast<const kv_u32x4*>(base + elem_off);
+    return *reinterpret_cast<const kv_u32x4*>(base + byte_off);
 }
 
 struct lane_consts {
     int r, quad;
-    uint32_t koff;   // element offset of this lane's K piece from the start of a 16-token half
-    uint32_t voff;   // element offset of this lane's V piece (token `quad` of a half)
-    uint32_t vstep;  // elements between V tokens 4 apart
+    uint32_t koff;   // byte offset of this lane's K piece from the start of a 16-token half
+    uint32_t voff;   // byte offset of this lane's V piece (token `quad` of a half)
+    uint32_t vstep;  // bytes between V tokens 4 apart
 };
 
 // Full tile: both halves lie in one block each; kb[h] points at (block, first slot of the half,
@@ -59,18 +61,18 @@ struct lane_consts {
 // arrangement (k[h][kk]); KMODE 1: K rows are fetched as they lie in memory, like V (k[h][i] =
 // bytes [16 r, +16) of token 16 h + 4 i + quad), and re-arranged through LDS before use.
 template <int KMODE>
-__device__ __forceinline__ void load_full(tile_regs& t, const uint16_t* const (&kb)[2],
-                                          int64_t plane_elems, const lane_consts& lc)
+__device__ __forceinline__ void load_full(tile_regs& t, const char* const (&kb)[2],
+                                          int64_t plane_bytes, const lane_consts& lc)
 {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            t.k[h][kk] = KMODE == 0 ? ld16(kb[h], lc.koff + kk * 32) : ld16(kb[h], lc.voff + kk * lc.vstep);
+            t.k[h][kk] = KMODE == 0 ? ld16(kb[h], lc.koff + kk * 64) : ld16(kb[h], lc.voff + kk * lc.vstep);
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const uint16_t* vb = kb[h] + plane_elems;
+        const char* vb = kb[h] + plane_bytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i) t.v[4 * h + i] = ld16(vb, lc.voff + i * lc.vstep);
     }
@@ -79,9 +81,9 @@ __device__ __forceinline__ void load_full(tile_regs& t, const uint16_t* const (&
 // Last, partial tile of a pair: rows past the last valid token are replaced by that token's row
 // (finite data; their scores are masked).  `last` = index of the last valid token in the tile.
 template <int KMODE>
-__device__ __forceinline__ void load_tail(tile_regs& t, const uint16_t* const (&kb)[2],
-                                          int64_t plane_elems, const lane_consts& lc, int last,
-                                          int token_stride)
+__device__ __forceinline__ void load_tail(tile_regs& t, const char* const (&kb)[2],
+                                          int64_t plane_bytes, const lane_consts& lc, int last,
+                                          int token_stride_bytes)
 {
     const int k_row = 4 * (lc.r & 3) + (lc.r >> 2);
 #pragma unroll
@@ -90,16 +92,16 @@ __device__ __forceinline__ void load_tail(tile_regs& t, const uint16_t* const (&
         // to the block of the last valid token by the caller and everything clamps to `last`
         const int first = (16 * h <= last) ? 16 * h : last;
         const int row = min(16 * h + k_row, last) - first;
-        const uint32_t off = (uint32_t)(row * token_stride + lc.quad * 8);
+        const uint32_t off = (uint32_t)(row * token_stride_bytes + lc.quad * 16);
         if (KMODE == 0) {
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = ld16(kb[h], off + kk * 32);
+            for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = ld16(kb[h], off + kk * 64);
         }
-        const uint16_t* vb = kb[h] + plane_elems;
+        const char* vb = kb[h] + plane_bytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int vrow = min(16 * h + 4 * i + lc.quad, last) - first;
-            const uint32_t voff = (uint32_t)(vrow * token_stride + lc.r * 8);
+            const uint32_t voff = (uint32_t)(vrow * token_stride_bytes + lc.r * 16);
             t.v[4 * h + i] = ld16(vb, voff);
             if (KMODE == 1) t.k[h][i] = ld16(kb[h], voff);
         }
@@ -237,6 +239,9 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
         }
         if (tid == kSkThreads - 1) s_prefix[a.batch] = before + incl;
         __syncthreads();
+        // the merge kernel needs the same numbers: the first workgroup leaves them in the workspace
+        if (blockIdx.x == 0)
+            for (int k = tid; k <= a.batch; k += kSkThreads) a.prefix_out[k] = s_prefix[k];
     }
 
     // ---- this wavefront's share ---------------------------------------------------------------
@@ -268,9 +273,11 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
     lane_consts lc;
     lc.r = lane & 15;
     lc.quad = lane >> 4;
-    lc.koff = (uint32_t)((4 * (lc.r & 3) + (lc.r >> 2)) * v.token_stride + lc.quad * 8);
-    lc.voff = (uint32_t)(lc.quad * v.token_stride + lc.r * 8);
-    lc.vstep = (uint32_t)(4 * v.token_stride);
+    const int token_stride_bytes = v.token_stride * 2;
+    const int64_t plane_bytes = v.plane_elems * 2;
+    lc.koff = (uint32_t)((4 * (lc.r & 3) + (lc.r >> 2)) * token_stride_bytes + lc.quad * 16);
+    lc.voff = (uint32_t)(lc.quad * token_stride_bytes + lc.r * 16);
+    lc.vstep = (uint32_t)(4 * token_stride_bytes);
     const int halves_per_block = v.block_tokens >> 4;  // capacity is a multiple of 16
     const int half_shift = v.block_shift >= 4 ? v.block_shift - 4 : -1;
 
@@ -280,15 +287,16 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
         const int n_full = n >> 5;                 // tiles of this pair with all 32 tokens valid
         const int full_end = min(seg_end, n_full);
         const int32_t* trow = a.table + (int64_t)s * a.table_stride;
-        const uint16_t* head_base = a.pool + v.head_off + hl * D;
+        const char* head_base = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D);
         const int last_block = (n - 1) / v.block_tokens;
 
         bf16x8 qb[4];
         {
-            const uint16_t* qrow = a.q + ((int64_t)s * v.n_q_local + hl * G + min(lc.r, G - 1)) * D;
+            const char* qrows = reinterpret_cast<const char*>(a.q + ((int64_t)s * v.n_q_local + hl * G) * D);
+            const uint32_t qoff = (uint32_t)(min(lc.r, G - 1) * (D * 2) + lc.quad * 16);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                kv_u32x4 raw = ld16_cached(qrow, kk * 32 + lc.quad * 8);
+                kv_u32x4 raw = ld16_cached(qrows, qoff + kk * 64);
                 if (lc.r >= G) raw = kv_u32x4{0u, 0u, 0u, 0u};
                 qb[kk] = as_bf16x8(raw);
             }
@@ -305,14 +313,14 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
             return half_shift >= 0 ? (hh >> half_shift) : hh / halves_per_block;
         };
         int idv = trow[min(half_block(id_base + lane), last_block)];
-        auto half_base = [&](int hh) -> const uint16_t* {
+        auto half_base = [&](int hh) -> const char* {
             if (hh - id_base >= 64) {
                 id_base = hh;
                 idv = trow[min(half_block(id_base + lane), last_block)];
             }
             const int blk = __builtin_amdgcn_readlane(idv, hh - id_base);
             const int slot0 = (hh - half_block(hh) * halves_per_block) << 4;
-            return head_base + (int64_t)blk * v.block_elems + (int64_t)slot0 * v.token_stride;
+            return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot0 * token_stride_bytes;
         };
 
         kv_u32x4* kstage = s_kstage + (KMODE == 1 ? wave * 512 : 0);
@@ -321,18 +329,18 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
         if (PIPE) {
             tile_regs tb;
             if (i < full_end) {
-                const uint16_t* kb[2] = {half_base(2 * i), half_base(2 * i + 1)};
-                load_full<KMODE>(ta, kb, v.plane_elems, lc);
+                const char* kb[2] = {half_base(2 * i), half_base(2 * i + 1)};
+                load_full<KMODE>(ta, kb, plane_bytes, lc);
             }
             while (i + 2 <= full_end) {
                 {
-                    const uint16_t* kb[2] = {half_base(2 * i + 2), half_base(2 * i + 3)};
-                    load_full<KMODE>(tb, kb, v.plane_elems, lc);
+                    const char* kb[2] = {half_base(2 * i + 2), half_base(2 * i + 3)};
+                    load_full<KMODE>(tb, kb, plane_bytes, lc);
                 }
                 compute_tile<false, KMODE>(ta, qb, st, a.scale_log2e, 31, lc.r, lc.quad, kstage);
                 if (i + 2 < full_end) {
-                    const uint16_t* kb[2] = {half_base(2 * i + 4), half_base(2 * i + 5)};
-                    load_full<KMODE>(ta, kb, v.plane_elems, lc);
+                    const char* kb[2] = {half_base(2 * i + 4), half_base(2 * i + 5)};
+                    load_full<KMODE>(ta, kb, plane_bytes, lc);
                 }
                 compute_tile<false, KMODE>(tb, qb, st, a.scale_log2e, 31, lc.r, lc.quad, kstage);
                 i += 2;
@@ -343,23 +351,23 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
             }
         } else {
             for (; i < full_end; ++i) {
-                const uint16_t* kb[2] = {half_base(2 * i), half_base(2 * i + 1)};
-                load_full<KMODE>(ta, kb, v.plane_elems, lc);
+                const char* kb[2] = {half_base(2 * i), half_base(2 * i + 1)};
+                load_full<KMODE>(ta, kb, plane_bytes, lc);
                 compute_tile<false, KMODE>(ta, qb, st, a.scale_log2e, 31, lc.r, lc.quad, kstage);
             }
         }
         if (seg_end > full_end) {
             // the pair's last tile, partly filled: tokens 32 * n_full .. n - 1
             const int last = n - 1 - 32 * n_full;  // 0..30
-            const uint16_t* kb[2];
+            const char* kb[2];
             kb[0] = half_base(2 * n_full);
             if (16 <= last) {
                 kb[1] = half_base(2 * n_full + 1);
             } else {
                 // second half empty: point it at the row of the last valid token
-                kb[1] = kb[0] + (int64_t)last * v.token_stride;
+                kb[1] = kb[0] + (int64_t)last * token_stride_bytes;
             }
-            load_tail<KMODE>(ta, kb, v.plane_elems, lc, last, v.token_stride);
+            load_tail<KMODE>(ta, kb, plane_bytes, lc, last, token_stride_bytes);
             compute_tile<true, KMODE>(ta, qb, st, a.scale_log2e, last, lc.r, lc.quad, kstage);
         }
 
@@ -411,33 +419,19 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
 
 // Merge the pieces of one (sequence, local query head), or write zeros for an empty context.
 // 256 lanes = 32 column groups of 4 elements x 8 slices of the piece list.  Recomputes the split
-// exactly as the main kernel did.
+// exactly as the main kernel did, from the per-sequence tile prefix that kernel left behind.
 __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_args a)
 {
     const int qi = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
     const int cg = tid & 31, slice = tid >> 5;
     const kv_view_dev& v = a.v;
     const int Hl = v.n_kv_local, G = a.group;
-    __shared__ int32_t s_red[4][2];
     __shared__ float s_max[4];
     __shared__ float s_acc[8][D];
     __shared__ float s_l[8];
-    // tiles before sequence s and in total
-    int before = 0, all = 0;
-    for (int k = tid; k < a.batch; k += 256) {
-        const int t = (a.ctx_lens[k] + 31) >> 5;
-        all += t;
-        if (k < s) before += t;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        before += __shfl_xor(before, off);
-        all += __shfl_xor(all, off);
-    }
-    if ((tid & 63) == 0) { s_red[tid >> 6][0] = before; s_red[tid >> 6][1] = all; }
-    __syncthreads();
-    before = s_red[0][0] + s_red[1][0] + s_red[2][0] + s_red[3][0];
-    all = s_red[0][1] + s_red[1][1] + s_red[2][1] + s_red[3][1];
+    // tiles before sequence s and in total, as computed by the main kernel
+    const int before = a.prefix_out[s];
+    const int all = a.prefix_out[a.batch];
 
     const int n = a.ctx_lens[s];
     uint16_t* dst = a.out + ((int64_t)s * v.n_q_local + qi) * D;
@@ -491,7 +485,8 @@ size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves)
     const size_t slots = (size_t)n_waves + (size_t)batch * view->n_kv_local;
     const size_t acc = (slots * view->group * D * 4 + 255) / 256 * 256;
     const size_t ml = (slots * view->group * 2 * 4 + 255) / 256 * 256;
-    return acc + ml;
+    const size_t prefix = ((size_t)(batch + 1) * 4 + 255) / 256 * 256;
+    return acc + ml + prefix;
 }
 
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st)
@@ -499,7 +494,9 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     const size_t slots = (size_t)a.n_waves + (size_t)a.batch * view->n_kv_local;
     const size_t acc = (slots * view->group * D * 4 + 255) / 256 * 256;
     a.part_acc = (float*)workspace;
+    const size_t ml = (slots * view->group * 2 * 4 + 255) / 256 * 256;
     a.part_ml = (float*)((char*)workspace + acc);
+    a.prefix_out = (int32_t*)((char*)workspace + acc + ml);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
     switch (kv_option_variant() & 3) {

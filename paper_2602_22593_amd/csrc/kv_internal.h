@@ -104,6 +104,7 @@ struct kv_streamk_args {
     int32_t n_waves;   // wavefronts launched (multiple of 4)
     float* part_acc;   // [n_waves + batch * n_kv_local][group][128]
     float* part_ml;    // [n_waves + batch * n_kv_local][group][2]
+    int32_t* prefix_out;  // [batch + 1] tiles of the sequences before s, written by the main kernel
 };
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

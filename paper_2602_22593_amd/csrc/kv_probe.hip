@@ -42,7 +42,43 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const kv_u32x
     for (; i < n_vec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// Paged variant: workgroup g streams whole blocks ids[g], ids[g + G], ... of `block_vecs`
+// 16-byte pieces each (the access pattern of a paged KV pool, with no arithmetic on the data).
+__global__ __launch_bounds__(kProbeThreads) void probe_read_blocks_kernel(
+    const kv_u32x4* __restrict__ pool, const int32_t* __restrict__ ids, int n_ids, int block_vecs,
+    uint32_t* sink)
+{
+    kv_u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int b = blockIdx.x; b < n_ids; b += gridDim.x) {
+        const kv_u32x4* src = pool + (size_t)ids[b] * block_vecs;
+        int i = threadIdx.x;
+        for (; i + (kProbeUnroll - 1) * kProbeThreads < block_vecs; i += kProbeUnroll * kProbeThreads) {
+            kv_u32x4 v[kProbeUnroll];
+#pragma unroll
+            for (int u = 0; u < kProbeUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + u * kProbeThreads);
+#pragma unroll
+            for (int u = 0; u < kProbeUnroll; ++u) acc ^= v[u];
+        }
+        for (; i < block_vecs; i += kProbeThreads) acc ^= __builtin_nontemporal_load(src + i);
+    }
+    const uint32_t f = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (f == 0x9e3779b9u && sink) sink[0] = f;
+}
+
 }  // namespace
+
+extern "C" int kv_probe_read_blocks(const void* pool, const int32_t* block_ids, int n_ids,
+                                    int64_t block_bytes, void* sink, int n_workgroups,
+                                    void* hip_stream)
+{
+    if (!pool || !block_ids || n_ids < 0 || block_bytes <= 0 || block_bytes % 16 != 0 || n_workgroups <= 0)
+        return KV_ERR_INVALID_ARG;
+    if (n_ids == 0) return KV_OK;
+    hipLaunchKernelGGL(probe_read_blocks_kernel, dim3((unsigned)n_workgroups), dim3(kProbeThreads), 0,
+                       (hipStream_t)hip_stream, (const kv_u32x4*)pool, block_ids, n_ids,
+                       (int)(block_bytes / 16), (uint32_t*)sink);
+    return kv_record_hip_error(hipGetLastError(), "kv_probe_read_blocks launch");
+}
 
 extern "C" int kv_probe_read(const void* src, size_t bytes, void* sink, int n_workgroups,
                              void* hip_stream)

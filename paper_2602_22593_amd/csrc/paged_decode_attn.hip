@@ -585,6 +585,7 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
         k.n_waves = n_waves;
         k.part_acc = nullptr;
         k.part_ml = nullptr;
+        k.prefix_out = nullptr;
         return kv_streamk_launch(k, view, workspace, st);
     }
 

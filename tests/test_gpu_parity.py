@@ -116,6 +116,40 @@ def test_even_split_kernel_variants(variant, wpc):
         kv.kv_set_option("waves_per_cu", 0)
 
 
+def test_one_long_sequence_cut_over_every_wavefront():
+    """A single (sequence, head) pair cut over every wavefront of the launch (about a thousand
+    pieces to merge), twice in a row on one uninitialised workspace, which then serves a call of
+    another kernel and another shape."""
+    w = wl.Workload("long1", 70, 32, 8, 128, 16, 2, "x", ())
+    ctx = np.array([40000, 3], dtype=np.int32)
+    triple = (LAYOUT_TP, 8, 3)
+    c = make_case(w, triple, ctx)
+    view = gpu_view(w, triple)
+    ws = torch.full((kv.paged_decode_attn_workspace_bytes(view, 2, 40000),), 0xAB, dtype=torch.uint8,
+                    device=DEV)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    q, pool = dev_u16(c.q), dev_u16(c.pool)
+    table, n = torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
+    for _ in range(2):
+        out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws)
+        torch.cuda.synchronize()
+        check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence")
+    # same workspace, chunked vector-ALU kernel on a different shape, then the even-split kernel again
+    c2 = make_case(TINY, (LAYOUT_TP, 2, 1))
+    ws2 = torch.full((max(ws.numel(), kv.paged_decode_attn_workspace_bytes(gpu_view(TINY, (LAYOUT_TP, 2, 1)), 4, 300)),),
+                     0xCD, dtype=torch.uint8, device=DEV)
+    kv.kv_set_option("chunk_tokens", 64)
+    out2 = kv.paged_decode_attn(dev_u16(c2.q), dev_u16(c2.pool), torch.from_numpy(c2.table).to(DEV),
+                                torch.from_numpy(c2.ctx).to(DEV), gpu_view(TINY, (LAYOUT_TP, 2, 1)), 300,
+                                workspace=ws2)
+    kv.kv_set_option("chunk_tokens", 0)
+    out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws2)
+    torch.cuda.synchronize()
+    check_close(bf16_bits_to_f64(out2.cpu().numpy().view(np.uint16)),
+                oracle.paged_decode(c2.view, c2.q, c2.pool, c2.table, c2.ctx), "tiny on shared workspace")
+    check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence after reuse")
+
+
 def test_explicit_scale_and_large_logits():
     """A scale of 1.0 (8x the default at d = 64) makes the softmax nearly one-hot: checks the
     running-max handling."""
