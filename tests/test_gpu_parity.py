@@ -150,6 +150,25 @@ def test_one_long_sequence_cut_over_every_wavefront():
     check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence after reuse")
 
 
+def test_repeated_calls_on_one_workspace():
+    """Five calls in a row on one workspace whose first contents are garbage, each compared with
+    the oracle: nothing a call leaves in the workspace may leak into the next one."""
+    w = wl.Workload("tuned", 71, 32, 8, 128, 16, 9, "x", ())
+    ctx = np.array([7000, 4100, 9000, 33, 6000, 8000, 3000, 5111, 1], dtype=np.int32)
+    for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)]:
+        c = make_case(w, triple, ctx)
+        view = gpu_view(w, triple)
+        ws = torch.full((kv.paged_decode_attn_workspace_bytes(view, len(ctx), 9000),), 0x5A, dtype=torch.uint8,
+                        device=DEV)
+        want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+        q, pool = dev_u16(c.q), dev_u16(c.pool)
+        table, n = torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
+        for call in range(5):
+            out = kv.paged_decode_attn(q, pool, table, n, view, 9000, workspace=ws)
+            torch.cuda.synchronize()
+            check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, f"{triple} call {call}")
+
+
 def test_explicit_scale_and_large_logits():
     """A scale of 1.0 (8x the default at d = 64) makes the softmax nearly one-hot: checks the
     running-max handling."""
