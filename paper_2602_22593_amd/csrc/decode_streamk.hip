@@ -418,17 +418,24 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
 }
 
 // Merge the pieces of one (sequence, local query head), or write zeros for an empty context.
-// 256 lanes = 32 column groups of 4 elements x 8 slices of the piece list.  Recomputes the split
-// exactly as the main kernel did, from the per-sequence tile prefix that kernel left behind.
+// The 256 lanes of a workgroup are column groups of 4 elements x slices of the piece list.  A
+// short list (the common case: a pair cut over a few wavefronts) is merged by one workgroup as
+// 32 column groups x 8 slices; a long one (one sequence cut over hundreds of wavefronts) by
+// kMergeSplit workgroups, each owning 128 / kMergeSplit columns as 8 column groups x 32 slices.
+// The host launches kMergeSplit workgroups per row only when the batch has few pairs for the
+// wavefronts launched (long lists are then the rule); in such a grid all but the first leave at
+// once for a short list.  Recomputes the split exactly as the main kernel did, from the per-sequence tile
+// prefix that kernel left behind.
+constexpr int kMergeSplit = 4;
+constexpr int kMergeLong = 24;  // pieces from which a list counts as long
 __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_args a)
 {
-    const int qi = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
-    const int cg = tid & 31, slice = tid >> 5;
+    const int qi = blockIdx.x, s = blockIdx.y, z = blockIdx.z, tid = threadIdx.x;
     const kv_view_dev& v = a.v;
     const int Hl = v.n_kv_local, G = a.group;
     __shared__ float s_max[4];
-    __shared__ float s_acc[8][D];
-    __shared__ float s_l[8];
+    __shared__ float s_acc[8 * D];
+    __shared__ float s_l[32];
     // tiles before sequence s and in total, as computed by the main kernel
     const int before = a.prefix_out[s];
     const int all = a.prefix_out[a.batch];
@@ -436,7 +443,7 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     const int n = a.ctx_lens[s];
     uint16_t* dst = a.out + ((int64_t)s * v.n_q_local + qi) * D;
     if (n == 0) {
-        if (tid < D) dst[tid] = 0;
+        if (z == 0 && tid < D) dst[tid] = 0;
         return;
     }
     const int tiles_s = (n + 31) >> 5;
@@ -446,7 +453,13 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     const int p0 = before * Hl + hl * tiles_s;          // first tile of the pair, flattened
     const int w_first = p0 / tpw, w_last = (p0 + tiles_s - 1) / tpw;
     if (w_first == w_last) return;                      // written in place by the main kernel
+    const bool wide = (gridDim.z > 1 && w_last - w_first + 1 >= kMergeLong);
+    if (!wide && z != 0) return;
     const int64_t pair = (int64_t)s * Hl + hl;
+    const int ncg = wide ? D / 4 / kMergeSplit : D / 4;  // column groups of this workgroup
+    const int cols = ncg * 4, nsl = 256 / ncg;
+    const int col0 = wide ? z * cols : 0;
+    const int cg = tid % ncg, slice = tid / ncg;
 
     float mm = kNegInf;
     for (int w = w_first + tid; w <= w_last; w += 256) mm = fmaxf(mm, a.part_ml[((w + pair) * G + g) * 2]);
@@ -458,23 +471,23 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
 
     float ll = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int w = w_first + slice; w <= w_last; w += 8) {
+    for (int w = w_first + slice; w <= w_last; w += nsl) {
         const int64_t rec = (w + pair) * G + g;
-        const float cw = fast_exp2(a.part_ml[rec * 2] - mm);
-        ll += a.part_ml[rec * 2 + 1] * cw;
-        acc += *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + cg * 4) * cw;
+        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
+        const float cw = fast_exp2(ml.x - mm);
+        ll += ml.y * cw;
+        acc += *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4) * cw;
     }
-    *reinterpret_cast<f32x4*>(&s_acc[slice][cg * 4]) = acc;
+    *reinterpret_cast<f32x4*>(&s_acc[slice * cols + cg * 4]) = acc;
     if (cg == 0) s_l[slice] = ll;
     __syncthreads();
-    if (tid < D) {
+    if (tid < cols) {
         float tot = 0.f, lt = 0.f;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            tot += s_acc[k][tid];
+        for (int k = 0; k < nsl; ++k) {
+            tot += s_acc[k * cols + tid];
             lt += s_l[k];
         }
-        dst[tid] = f32_to_bf16(tot / lt);
+        dst[col0 + tid] = f32_to_bf16(tot / lt);
     }
 }
 
@@ -509,7 +522,10 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     int rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn launch");
     if (rc) return rc;
     slot = kv_prof_begin(KV_PROF_DECODE_MERGE, st);
-    hipLaunchKernelGGL(decode_streamk_merge_kernel, dim3((unsigned)view->n_q_local, (unsigned)a.batch),
+    // eight or more pieces per pair on average: expect long lists, split their columns
+    const bool few_pairs = (int64_t)a.batch * view->n_kv_local * 8 <= a.n_waves;
+    hipLaunchKernelGGL(decode_streamk_merge_kernel,
+                       dim3((unsigned)view->n_q_local, (unsigned)a.batch, few_pairs ? (unsigned)kMergeSplit : 1u),
                        dim3(256), 0, st, a);
     kv_prof_end(KV_PROF_DECODE_MERGE, slot, st);
     return kv_record_hip_error(hipGetLastError(), "paged_decode_attn merge launch");
