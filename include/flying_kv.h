@@ -130,6 +130,34 @@ int paged_decode_attn(const void* q, void* out, const void* kv_pool, int64_t n_p
                       size_t workspace_bytes, void* hip_stream);
 
 /*
+ * paged_decode_attn_mixed -- paged_decode_attn for a batch whose sequences do not all keep
+ * their KV in the same block layout (Sec. 5.2.3: blocks written under different parallelism
+ * modes coexist in one pool; Sec. 4.2.3: the kernels are told each request's stride and block
+ * capacity).  Sequence s is read under views[view_ids[s]].  The result is the one
+ * paged_decode_attn defines, sequence by sequence, under that sequence's view.
+ *
+ * Every view must have the geometry, TP degree p and rank r of views[0]: the batch runs on one
+ * rank, so all sequences expose the same heads (q, out: [batch][n_q_local][head_dim] as above)
+ * and the views differ only in layout -- e.g. views[0] = (TP, p, r) for requests admitted in TP
+ * mode and views[1] = (DP, p, r), the same head slice read in place from blocks a DP engine
+ * wrote, for requests taken over without a repack.
+ *
+ *   view_ids     device, int32 [batch], each in [0, n_views) (values outside are clamped)
+ *   views        host array of n_views views, 1 <= n_views <= 4
+ *   block_table  row s is indexed with the block capacity of sequence s's view;
+ *                block_table_stride must cover max_ctx_len under the smallest capacity
+ *   workspace    at least paged_decode_attn_workspace_bytes(views[0], batch, max_ctx_len)
+ * Other arguments and errors as paged_decode_attn; in addition KV_ERR_INVALID_ARG for views
+ * that disagree in geometry, p or r, and KV_ERR_UNSUPPORTED when n_views > 1 and the shape is
+ * not served by the matrix-core kernel (head_dim 128, group <= 16, batch <= 2048).
+ */
+int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
+                            const int32_t* block_table, int64_t block_table_stride,
+                            const int32_t* ctx_lens, const int32_t* view_ids, int batch,
+                            int max_ctx_len, const kv_view* const* views, int n_views, float scale,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * kv_repack -- move KV rows between two arrangements inside one pool, bit-exactly.  This
  * is what a DP->TP or TP->DP transition needs when the existing blocks cannot simply be
  * re-interpreted (the paper's Soft Preempt recomputes the cache instead, Sec. 5.2.2; a

@@ -106,6 +106,29 @@ def paged_decode(view: View, q, pool, table, ctx_lens, scale: float = 0.0) -> np
     return out
 
 
+def paged_decode_mixed(views, view_ids, q, pool, table, ctx_lens, scale: float = 0.0) -> np.ndarray:
+    """Decode attention for a batch in which sequence s keeps its KV as ``views[view_ids[s]]``
+    says (blocks written under different parallelism modes coexist in one pool, paper
+    Sec. 5.2.3; each request carries its own stride and block capacity, Sec. 4.2.3).
+
+    By definition the result is, sequence by sequence, what ``paged_decode`` gives under that
+    sequence's view: computed exactly so, one pass per view with the other sequences' lengths
+    set to zero.  All views must expose the same heads (same TP degree and rank).
+    """
+    ctx_lens = np.asarray(ctx_lens, dtype=np.int32)
+    view_ids = np.asarray(view_ids)
+    infos = [v.query() for v in views]
+    assert all((i["n_q_local"], i["kv_head0"]) == (infos[0]["n_q_local"], infos[0]["kv_head0"]) for i in infos)
+    out = np.zeros((len(ctx_lens), infos[0]["n_q_local"], views[0].geom.head_dim), dtype=np.float64)
+    for k, v in enumerate(views):
+        mine = view_ids == k
+        if not mine.any():
+            continue
+        part = paged_decode(v, q, pool, table, np.where(mine, ctx_lens, 0).astype(np.int32), scale)
+        out[mine] = part[mine]
+    return out
+
+
 def paged_decode_pairs(view: View, q, pool, table, ctx_lens, pair_seq, pair_head,
                        scale: float = 0.0) -> np.ndarray:
     """Rows for selected (sequence, local query head) pairs: out[n_pairs][d] fp64."""

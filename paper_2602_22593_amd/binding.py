@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
     L.paged_decode_attn_workspace_bytes.restype = C.c_size_t
     L.paged_decode_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp, C.c_float,
                                     vp, C.c_size_t, vp]
+    L.paged_decode_attn_mixed.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, vp, C.c_int,
+                                          C.c_float, vp, C.c_size_t, vp]
     L.kv_repack.argtypes = [vp, i64, vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp]
     L.kv_append.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp, C.c_int, vp]
     L.kv_validate_tables.argtypes = [vp, i64, vp, i64, vp, C.c_int, vp, vp, i64, vp]
@@ -178,6 +180,37 @@ def paged_decode_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch
         float(scale), _dev(workspace, (torch.uint8,), "workspace"),
         workspace.numel(), _stream_ptr(stream))
     _check(rc, "paged_decode_attn")
+    return out
+
+
+def paged_decode_attn_mixed(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch.Tensor,
+                            ctx_lens: torch.Tensor, view_ids: torch.Tensor, views, max_ctx_len: int,
+                            out: Optional[torch.Tensor] = None, scale: float = 0.0,
+                            workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Decode attention for a batch whose sequence s keeps its KV as ``views[view_ids[s]]`` says.
+
+    All views share geometry, TP degree and rank (same local heads); they differ in block layout.
+    """
+    batch = int(ctx_lens.shape[0])
+    v0 = views[0]
+    if tuple(q.shape) != (batch, v0.n_q_local, v0.head_dim):
+        raise ValueError(f"q has shape {tuple(q.shape)}, expected {(batch, v0.n_q_local, v0.head_dim)}")
+    if out is None:
+        out = torch.empty_like(q)
+    if block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError("block_table must be [batch][max_blocks]")
+    n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // v0.block_bytes
+    need = paged_decode_attn_workspace_bytes(v0, batch, max_ctx_len)
+    if workspace is None:
+        workspace = _workspace(q.device, need)
+    handles = (C.c_void_p * len(views))(*[v.handle for v in views])
+    rc = lib().paged_decode_attn_mixed(
+        _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),
+        n_pool_blocks, _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
+        _dev(ctx_lens, (torch.int32,), "ctx_lens"), _dev(view_ids, (torch.int32,), "view_ids"), batch,
+        int(max_ctx_len), C.cast(handles, C.c_void_p), len(views), float(scale),
+        _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream_ptr(stream))
+    _check(rc, "paged_decode_attn_mixed")
     return out
 
 

@@ -193,7 +193,7 @@ __device__ __forceinline__ void compute_tile(const tile_regs& t, const bf16x8 (&
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-template <int KMODE, int PIPE>
+template <int KMODE, int PIPE, bool MIXED>
 __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kernel(kv_streamk_args a)
 {
     __shared__ kv_u32x4 s_kstage[KMODE == 1 ? kSkWaves * 512 : 1];
@@ -273,22 +273,33 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
     lane_consts lc;
     lc.r = lane & 15;
     lc.quad = lane >> 4;
-    const int token_stride_bytes = v.token_stride * 2;
     const int64_t plane_bytes = v.plane_elems * 2;
-    lc.koff = (uint32_t)((4 * (lc.r & 3) + (lc.r >> 2)) * token_stride_bytes + lc.quad * 16);
-    lc.voff = (uint32_t)(lc.quad * token_stride_bytes + lc.r * 16);
-    lc.vstep = (uint32_t)(4 * token_stride_bytes);
-    const int halves_per_block = v.block_tokens >> 4;  // capacity is a multiple of 16
-    const int half_shift = v.block_shift >= 4 ? v.block_shift - 4 : -1;
+    // layout of the current sequence's blocks (MIXED: looked up per sequence; else the view's own)
+    kv_layout_dev lay = {v.block_tokens, v.block_shift, v.token_stride, v.head_off};
+    int token_stride_bytes, halves_per_block, half_shift;
+    auto use_layout = [&]() {
+        token_stride_bytes = lay.token_stride * 2;
+        lc.koff = (uint32_t)((4 * (lc.r & 3) + (lc.r >> 2)) * token_stride_bytes + lc.quad * 16);
+        lc.voff = (uint32_t)(lc.quad * token_stride_bytes + lc.r * 16);
+        lc.vstep = (uint32_t)(4 * token_stride_bytes);
+        halves_per_block = lay.block_tokens >> 4;  // capacity is a multiple of 16
+        half_shift = lay.block_shift >= 4 ? lay.block_shift - 4 : -1;
+    };
+    use_layout();
 
     while (x0 < x1) {
+        if (MIXED) {
+            const int vid = min(max(uniform(a.view_ids[s]), 0), a.n_views - 1);
+            lay = a.lay[vid];
+            use_layout();
+        }
         const int n = uniform(s_ctx[s]);
         const int seg_end = min(tiles_s, tile + (x1 - x0));
         const int n_full = n >> 5;                 // tiles of this pair with all 32 tokens valid
         const int full_end = min(seg_end, n_full);
         const int32_t* trow = a.table + (int64_t)s * a.table_stride;
-        const char* head_base = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D);
-        const int last_block = (n - 1) / v.block_tokens;
+        const char* head_base = reinterpret_cast<const char*>(a.pool + lay.head_off + hl * D);
+        const int last_block = (n - 1) / lay.block_tokens;
 
         bf16x8 qb[4];
         {
@@ -512,11 +523,14 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     a.prefix_out = (int32_t*)((char*)workspace + acc + ml);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
+    if (a.view_ids) {
+        hipLaunchKernelGGL((decode_streamk_kernel<1, 1, true>), grid, block, 0, st, a);
+    } else
     switch (kv_option_variant() & 3) {
-        case 0: hipLaunchKernelGGL((decode_streamk_kernel<1, 1>), grid, block, 0, st, a); break;
-        case 1: hipLaunchKernelGGL((decode_streamk_kernel<0, 1>), grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((decode_streamk_kernel<1, 0>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((decode_streamk_kernel<0, 0>), grid, block, 0, st, a); break;
+        case 0: hipLaunchKernelGGL((decode_streamk_kernel<1, 1, false>), grid, block, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((decode_streamk_kernel<0, 1, false>), grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((decode_streamk_kernel<1, 0, false>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((decode_streamk_kernel<0, 0, false>), grid, block, 0, st, a); break;
     }
     kv_prof_end(KV_PROF_DECODE_MAIN, slot, st);
     int rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn launch");

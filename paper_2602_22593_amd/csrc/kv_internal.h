@@ -90,6 +90,12 @@ void kv_prof_end(int which, int slot, hipStream_t st);
 
 // ---- matrix-core decode kernel with an even split over resident wavefronts --------------------
 #define KV_STREAMK_MAX_BATCH 2048
+#define KV_MAX_MIXED_VIEWS 4
+// The part of a view that may differ between the sequences of one batch: how the tokens of a
+// sequence are laid out in its blocks.  Head counts and the head range are common to the batch.
+struct kv_layout_dev {
+    int32_t block_tokens, block_shift, token_stride, head_off;
+};
 struct kv_streamk_args {
     const uint16_t* q;
     uint16_t* out;
@@ -105,6 +111,9 @@ struct kv_streamk_args {
     float* part_acc;   // [n_waves + batch * n_kv_local][group][128]
     float* part_ml;    // [n_waves + batch * n_kv_local][group][2]
     int32_t* prefix_out;  // [batch + 1] tiles of the sequences before s, written by the main kernel
+    const int32_t* view_ids;  // [batch] index into lay[] per sequence, or null: every sequence under v
+    int32_t n_views;
+    kv_layout_dev lay[KV_MAX_MIXED_VIEWS];
 };
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

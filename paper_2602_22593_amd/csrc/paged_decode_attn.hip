@@ -14,6 +14,7 @@
 //                       the matrix cores (16x16x32 bf16 MFMA), the query group padded to 16.
 //   decode_valu_kernel  any G in {1,2,4,8}, head_dim 64 or 128, any block capacity: vector ALU.
 #include <math.h>
+#include <string.h>
 
 #include "kv_internal.h"
 
@@ -531,6 +532,46 @@ size_t chunked_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
     return align_up((size_t)recs * view->geom.head_dim * 4, 256) + align_up((size_t)recs * 2 * 4, 256);
 }
 
+// The even-split matrix-core kernel.  views/view_ids non-null: sequence s is laid out as
+// views[view_ids[s]] says (all of them expose the same heads as `view`).
+static int launch_streamk(const void* q, void* out, const void* kv_pool, const int32_t* block_table,
+                          int64_t block_table_stride, const int32_t* ctx_lens, int batch,
+                          int max_ctx_len, const kv_view* view, float sc, void* workspace,
+                          size_t workspace_bytes, hipStream_t st, const int32_t* view_ids,
+                          const kv_view* const* views, int n_views)
+{
+    // tiles of 32 tokens over all (sequence, head) pairs must fit 31 bits
+    if (((int64_t)max_ctx_len / 32 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
+        return KV_ERR_UNSUPPORTED;
+    const int n_waves = streamk_waves();
+    const size_t need_sk = kv_streamk_workspace_bytes(view, batch, n_waves);
+    if (!workspace) return KV_ERR_INVALID_ARG;
+    if (workspace_bytes < need_sk) return KV_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return KV_ERR_INVALID_ARG;
+    kv_streamk_args k;
+    k.q = (const uint16_t*)q;
+    k.out = (uint16_t*)out;
+    k.pool = (const uint16_t*)kv_pool;
+    k.table = block_table;
+    k.table_stride = block_table_stride;
+    k.ctx_lens = ctx_lens;
+    k.v = kv_view_to_dev(view);
+    k.scale_log2e = sc * 1.4426950408889634f;
+    k.group = view->group;
+    k.batch = batch;
+    k.n_waves = n_waves;
+    k.part_acc = nullptr;
+    k.part_ml = nullptr;
+    k.prefix_out = nullptr;
+    k.view_ids = view_ids;
+    k.n_views = view_ids ? n_views : 1;
+    for (int i = 0; i < KV_MAX_MIXED_VIEWS; ++i) {
+        const kv_view_dev d = kv_view_to_dev(view_ids && i < n_views ? views[i] : view);
+        k.lay[i] = kv_layout_dev{d.block_tokens, d.block_shift, d.token_stride, d.head_off};
+    }
+    return kv_streamk_launch(k, view, workspace, st);
+}
+
 }  // namespace
 
 extern "C" size_t paged_decode_attn_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
@@ -562,32 +603,9 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     hipStream_t st = (hipStream_t)hip_stream;
 
-    if (kernel == 1 && max_ctx_len > 0) {
-        // tiles of 32 tokens over all (sequence, head) pairs must fit 31 bits
-        if (((int64_t)max_ctx_len / 32 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
-            return KV_ERR_UNSUPPORTED;
-        const int n_waves = streamk_waves();
-        const size_t need_sk = kv_streamk_workspace_bytes(view, batch, n_waves);
-        if (!workspace) return KV_ERR_INVALID_ARG;
-        if (workspace_bytes < need_sk) return KV_ERR_WORKSPACE;
-        if (((uintptr_t)workspace & 255u) != 0) return KV_ERR_INVALID_ARG;
-        kv_streamk_args k;
-        k.q = (const uint16_t*)q;
-        k.out = (uint16_t*)out;
-        k.pool = (const uint16_t*)kv_pool;
-        k.table = block_table;
-        k.table_stride = block_table_stride;
-        k.ctx_lens = ctx_lens;
-        k.v = kv_view_to_dev(view);
-        k.scale_log2e = sc * 1.4426950408889634f;
-        k.group = view->group;
-        k.batch = batch;
-        k.n_waves = n_waves;
-        k.part_acc = nullptr;
-        k.part_ml = nullptr;
-        k.prefix_out = nullptr;
-        return kv_streamk_launch(k, view, workspace, st);
-    }
+    if (kernel == 1 && max_ctx_len > 0)
+        return launch_streamk(q, out, kv_pool, block_table, block_table_stride, ctx_lens, batch,
+                              max_ctx_len, view, sc, workspace, workspace_bytes, st, nullptr, nullptr, 1);
 
     const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
     int64_t max_chunks = ((int64_t)max_ctx_len + chunk - 1) / chunk;
@@ -639,4 +657,40 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
         rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn merge launch");
     }
     return rc;
+}
+
+
+extern "C" int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool,
+                                       int64_t n_pool_blocks, const int32_t* block_table,
+                                       int64_t block_table_stride, const int32_t* ctx_lens,
+                                       const int32_t* view_ids, int batch, int max_ctx_len,
+                                       const kv_view* const* views, int n_views, float scale,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!views || n_views < 1 || n_views > KV_MAX_MIXED_VIEWS) return KV_ERR_INVALID_ARG;
+    for (int i = 0; i < n_views; ++i)
+        if (!kv_view_ok(views[i])) return KV_ERR_INVALID_ARG;
+    const kv_view* v0 = views[0];
+    int min_block = v0->block_tokens;
+    for (int i = 1; i < n_views; ++i) {
+        const kv_view* v = views[i];
+        // one pool, one head range: the views may differ only in how a block lays its tokens out
+        if (memcmp(&v->geom, &v0->geom, sizeof(kv_geometry)) != 0 || v->p != v0->p || v->r != v0->r)
+            return KV_ERR_INVALID_ARG;
+        if (v->block_tokens < min_block) min_block = v->block_tokens;
+    }
+    if (n_views == 1 || batch <= 0 || max_ctx_len <= 0)
+        return paged_decode_attn(q, out, kv_pool, n_pool_blocks, block_table, block_table_stride,
+                                 ctx_lens, batch, max_ctx_len, v0, scale, workspace, workspace_bytes,
+                                 hip_stream);
+    if (n_pool_blocks < 0 || block_table_stride < 0) return KV_ERR_INVALID_ARG;
+    if (!q || !out || !ctx_lens || !view_ids || !kv_pool || !block_table) return KV_ERR_INVALID_ARG;
+    if (block_table_stride < ((int64_t)max_ctx_len + min_block - 1) / min_block) return KV_ERR_INVALID_ARG;
+    for (int i = 0; i < n_views; ++i)
+        if (pick_kernel(views[i], batch) != 1) return KV_ERR_UNSUPPORTED;
+    if (batch > 65535 || v0->n_kv_local > 65535) return KV_ERR_UNSUPPORTED;
+    const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)v0->geom.head_dim);
+    return launch_streamk(q, out, kv_pool, block_table, block_table_stride, ctx_lens, batch, max_ctx_len,
+                          v0, sc, workspace, workspace_bytes, (hipStream_t)hip_stream, view_ids, views,
+                          n_views);
 }

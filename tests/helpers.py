@@ -74,6 +74,52 @@ def make_case(w: wl.Workload, view_triple, ctx: Optional[np.ndarray] = None, sla
                 q_slice(q_full, info, view.rank), table, pool)
 
 
+@dataclass
+class MixedCase:
+    w: wl.Workload
+    views: list              # oracle.View per layout
+    view_ids: np.ndarray     # int32[batch]
+    ctx: np.ndarray
+    seq_off: np.ndarray
+    K: np.ndarray
+    V: np.ndarray
+    q_full: np.ndarray
+    q: np.ndarray            # the rank's query heads (same for every view)
+    table: np.ndarray        # row s indexed with the block capacity of sequence s's view
+    pool: np.ndarray
+
+
+def make_mixed_case(w: wl.Workload, triples, view_ids, ctx, slack: float = 1.3) -> MixedCase:
+    """One pool in which sequence s is stored under ``triples[view_ids[s]]`` (all with the same TP
+    degree and rank); NaN-poisoned wherever no valid token lies."""
+    geom = geometry(w)
+    views = [oracle.View(geom, *t) for t in triples]
+    infos = [v.query() for v in views]
+    ctx = np.asarray(ctx, dtype=np.int32)
+    view_ids = np.asarray(view_ids, dtype=np.int32)
+    w_eff = wl.Workload(w.name, w.index, w.n_q_heads, w.n_kv_heads, w.head_dim, w.base_block_size,
+                        len(ctx), w.lengths, w.views)
+    K, V = wl.logical_kv(w_eff, ctx)
+    q_full = wl.queries(w_eff)
+    caps = np.array([infos[k]["block_tokens"] for k in view_ids], dtype=np.int64)
+    need = (ctx.astype(np.int64) + caps - 1) // caps
+    perm = wl.shuffled_pool(max(int(need.sum()), 1), slack, wl.generator(w.index, wl.SUB_PERM))
+    # wide enough for the longest sequence under the smallest capacity (what the ABI asks for)
+    min_cap = min(i["block_tokens"] for i in infos)
+    cols = max(int(need.max()), (int(ctx.max()) + min_cap - 1) // min_cap, 1)
+    table = np.full((len(ctx), cols), -1, dtype=np.int32)
+    used = 0
+    for s, k in enumerate(need):
+        table[s, :k] = perm[used:used + int(k)]
+        used += int(k)
+    pool = wl.poisoned_pool(len(perm), infos[0]["block_bytes"] // 2)
+    seq_off = wl.seq_offsets(ctx)
+    for k, v in enumerate(views):
+        oracle.scatter(v, pool, table, np.where(view_ids == k, ctx, 0).astype(np.int32), seq_off, K, V)
+    return MixedCase(w_eff, views, view_ids, ctx, seq_off, K, V, q_full,
+                     q_slice(q_full, infos[0], views[0].rank), table, pool)
+
+
 def textbook_attention(q_full: np.ndarray, K: np.ndarray, V: np.ndarray, seq_off: np.ndarray,
                        n_q_heads: int, n_kv_heads: int, scale: float) -> np.ndarray:
     """softmax(scale * q K^T) V per sequence and head with numpy matmuls, fp64.

@@ -135,6 +135,41 @@ def test_null_and_size_checks_without_a_gpu():
     assert L.kv_append(None, 10, v.handle, fake, fake, fake, 8, fake, 1, None) == kv.KV_ERR_INVALID_ARG
 
 
+def test_mixed_entry_point_checks_without_a_gpu():
+    """paged_decode_attn_mixed validates its view list on the host."""
+    L = kv.lib()
+    fake = C.c_void_p(256)
+    tp = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_TP, 4, 1)
+    alias = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 4, 1)
+    other_rank = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 4, 2)
+    other_p = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_TP, 2, 1)
+    other_geom = kv.kv_view_create(64, 8, 128, 16, kv.KV_LAYOUT_TP, 4, 1)
+
+    def call(views, n=None, stride=2048, ws=1 << 30, ids=fake, batch=2, max_ctx=16384):
+        arr = (C.c_void_p * len(views))(*[v.handle if v is not None else None for v in views])
+        return L.paged_decode_attn_mixed(fake, fake, fake, 10, fake, stride, fake, ids, batch, max_ctx,
+                                         C.cast(arr, C.c_void_p), len(views) if n is None else n, 0.0,
+                                         fake, ws, None)
+
+    assert L.paged_decode_attn_mixed(fake, fake, fake, 10, fake, 8, fake, fake, 2, 16, None, 1, 0.0, fake,
+                                     1 << 20, None) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, alias], n=0) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, alias, tp, alias, tp]) == kv.KV_ERR_INVALID_ARG        # more than 4 views
+    assert call([tp, None]) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, other_rank]) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, other_p]) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, other_geom]) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, alias], ids=None) == kv.KV_ERR_INVALID_ARG
+    # 16384 tokens need 1024 columns under the 16-token alias layout (256 would do for TP alone)
+    assert call([tp, alias], stride=1023) == kv.KV_ERR_INVALID_ARG
+    assert call([tp, alias], ws=1024) == kv.KV_ERR_WORKSPACE
+    assert call([tp, alias], batch=0) == kv.KV_OK
+    # head_dim 64 is served by the plain call only
+    a64 = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_TP, 2, 0)
+    b64 = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_DP, 2, 0)
+    assert call([a64, b64]) == kv.KV_ERR_UNSUPPORTED
+
+
 def test_unsupported_shapes_are_reported():
     L = kv.lib()
     fake = C.c_void_p(256)

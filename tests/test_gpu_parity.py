@@ -10,7 +10,7 @@ from oracle import LAYOUT_DP, LAYOUT_TP
 from paper_2602_22593_amd import binding as kv
 from paper_2602_22593_amd import workloads as wl
 
-from helpers import bf16_bits_to_f64, geometry, make_case, q_slice
+from helpers import make_mixed_case, bf16_bits_to_f64, geometry, make_case, q_slice
 
 pytestmark = pytest.mark.gpu
 
@@ -167,6 +167,40 @@ def test_repeated_calls_on_one_workspace():
             out = kv.paged_decode_attn(q, pool, table, n, view, 9000, workspace=ws)
             torch.cuda.synchronize()
             check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, f"{triple} call {call}")
+
+
+@pytest.mark.parametrize("p,r", [(2, 1), (4, 2), (8, 0)])
+def test_mixed_layouts_in_one_launch(p, r):
+    """One launch over a batch whose sequences are stored under two layouts of one pool: the TP
+    layout of rank r and rank r's head slice inside DP-layout blocks (requests taken over from a
+    DP engine without repacking).  Lengths make wavefront ranges cross sequences of different
+    layouts; pool NaN-poisoned outside valid tokens."""
+    w = wl.Workload("mixed", 73, 32, 8, 128, 16, 12, "x", ())
+    ctx = np.array([1, 31, 4100, 33, 0, 511, 513, 2049, 64, 7000, 96, 1500], dtype=np.int32)
+    ids = np.array([0, 1, 1, 0, 1, 0, 0, 1, 1, 0, 1, 1], dtype=np.int32)
+    triples = [(LAYOUT_TP, p, r), (LAYOUT_DP, p, r)]
+    c = make_mixed_case(w, triples, ids, ctx)
+    want = oracle.paged_decode_mixed(c.views, c.view_ids, c.q, c.pool, c.table, c.ctx)
+    views = [gpu_view(w, t) for t in triples]
+    for order in (0, 1):   # the same batch with the view list (and ids) swapped
+        vs = views[::-1] if order else views
+        vid = (1 - ids) if order else ids
+        out = kv.paged_decode_attn_mixed(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                                         torch.from_numpy(c.ctx).to(DEV),
+                                         torch.from_numpy(vid.astype(np.int32)).to(DEV), vs, int(ctx.max()))
+        torch.cuda.synchronize()
+        got = bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
+        check_close(got, want, f"mixed p={p} r={r} order {order}")
+        assert (got[4] == 0).all()
+    # a one-view list is the plain call
+    c1 = make_case(w, triples[0], ctx)
+    one = kv.paged_decode_attn_mixed(dev_u16(c1.q), dev_u16(c1.pool), torch.from_numpy(c1.table).to(DEV),
+                                     torch.from_numpy(c1.ctx).to(DEV),
+                                     torch.zeros(len(ctx), dtype=torch.int32, device=DEV), views[:1],
+                                     int(ctx.max()))
+    torch.cuda.synchronize()
+    check_close(bf16_bits_to_f64(one.cpu().numpy().view(np.uint16)),
+                oracle.paged_decode(c1.view, c1.q, c1.pool, c1.table, c1.ctx), "one view")
 
 
 def test_explicit_scale_and_large_logits():

@@ -14,7 +14,7 @@ import oracle
 from oracle import LAYOUT_DP, LAYOUT_TP, Geometry, View
 from paper_2602_22593_amd import workloads as wl
 
-from helpers import Case, bf16_bits_to_f64, make_case, q_slice, textbook_attention
+from helpers import Case, bf16_bits_to_f64, make_case, make_mixed_case, q_slice, textbook_attention
 
 TINY = wl.WORKLOADS["tiny"]
 TINY_VIEWS = [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 0), (LAYOUT_TP, 2, 1), (LAYOUT_DP, 2, 1)]
@@ -38,6 +38,26 @@ def test_paged_equals_textbook_on_logical_tensors(view):
     got = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
     assert np.isfinite(got).all()
     np.testing.assert_allclose(got, rank_rows(want, c.info, c.view.rank), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("rank", [0, 1])
+def test_mixed_layouts_in_one_batch_equal_textbook(rank):
+    """Sequences stored under two layouts in one pool (the TP layout of rank r, and rank r's head
+    slice inside DP-layout blocks), one block table whose rows are indexed with each sequence's own
+    block capacity: the per-sequence-view oracle must equal numpy's textbook attention on the
+    logical tensors, whatever the layout.  A wrong capacity, stride or head offset for either
+    layout reads NaN poison or another head."""
+    ctx = np.array([17, 64, 150, 300, 1, 33, 0, 95], dtype=np.int32)
+    ids = np.array([0, 1, 1, 0, 1, 0, 1, 0], dtype=np.int32)
+    c = make_mixed_case(TINY, [(LAYOUT_TP, 2, rank), (LAYOUT_DP, 2, rank)], ids, ctx)
+    want = textbook_attention(c.q_full, c.K, c.V, c.seq_off, TINY.n_q_heads, TINY.n_kv_heads,
+                              1.0 / np.sqrt(TINY.head_dim))
+    got = oracle.paged_decode_mixed(c.views, c.view_ids, c.q, c.pool, c.table, c.ctx)
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got, rank_rows(want, c.views[0].query(), rank), rtol=0, atol=1e-12)
+    # reading every sequence under one layout must NOT work (the pin can tell the layouts apart)
+    wrong = oracle.paged_decode(c.views[0], c.q, c.pool, c.table, c.ctx)
+    assert not np.isfinite(wrong[ids == 1][ctx[ids == 1] > 0]).all()
 
 
 def test_dense_oracle_equals_textbook_and_paged():
