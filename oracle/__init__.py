@@ -129,6 +129,43 @@ def paged_decode_mixed(views, view_ids, q, pool, table, ctx_lens, scale: float =
     return out
 
 
+def paged_prefill_rows(view: View, q, pool, table, ctx_lens, q_off, row_q, row_head,
+                       scale: float = 0.0) -> np.ndarray:
+    """Causal multi-token attention for selected (row of q, local head) pairs: out[n][d] fp64.
+
+    q is [total_q][Hql][d]; sequence s owns rows [q_off[s], q_off[s+1]), which are the LAST
+    q_len tokens of its ctx_lens[s] cached ones; each attends to every token up to itself.
+    """
+    info = view.query()
+    d = view.geom.head_dim
+    batch = int(len(ctx_lens))
+    q_off = np.ascontiguousarray(q_off, dtype=np.int64)
+    assert q.shape == (int(q_off[-1]), info["n_q_local"], d), q.shape
+    table = np.ascontiguousarray(table, dtype=np.int32).reshape(batch, -1)
+    rq = np.ascontiguousarray(row_q, dtype=np.int64)
+    rh = np.ascontiguousarray(row_head, dtype=np.int32)
+    out = np.empty((rq.shape[0], d), dtype=np.float64)
+    rc = lib().oracle_paged_prefill_rows(*view._args(), _p(q, np.uint16), _p(pool.reshape(-1), np.uint16),
+                                         _p(table, np.int32), C.c_int64(table.shape[1]),
+                                         _p(np.ascontiguousarray(ctx_lens, dtype=np.int32), np.int32),
+                                         _p(q_off, np.int64), C.c_int32(batch), _p(rq, np.int64),
+                                         _p(rh, np.int32), C.c_int64(rq.shape[0]), C.c_double(scale),
+                                         _p(out, np.float64))
+    if rc:
+        raise ValueError(f"oracle_paged_prefill_rows rc={rc}")
+    return out
+
+
+def paged_prefill(view: View, q, pool, table, ctx_lens, q_off, scale: float = 0.0) -> np.ndarray:
+    """All rows: out[total_q][Hql][d] fp64 (see paged_prefill_rows)."""
+    info = view.query()
+    total, hql = int(q_off[-1]), info["n_q_local"]
+    rq = np.repeat(np.arange(total, dtype=np.int64), hql)
+    rh = np.tile(np.arange(hql, dtype=np.int32), total)
+    return paged_prefill_rows(view, q, pool, table, ctx_lens, q_off, rq, rh, scale).reshape(
+        total, hql, view.geom.head_dim)
+
+
 def paged_decode_pairs(view: View, q, pool, table, ctx_lens, pair_seq, pair_head,
                        scale: float = 0.0) -> np.ndarray:
     """Rows for selected (sequence, local query head) pairs: out[n_pairs][d] fp64."""

@@ -9,6 +9,8 @@
  *   - paged single-query (decode) attention through such a view
  *     (Sec. 2.1 "Attention Layer": softmax attention over the cached K/V;
  *     Sec. 4.1.1: a TP rank owns a disjoint, contiguous subset of heads),
+ *   - paged multi-token causal attention through a view (a prefill chunk or
+ *     the recompute of Soft Preempt, Sec. 5.2.2; chunked prefill, Sec. 3),
  *   - scatter / gather of logical K/V rows to / from pool blocks (the stand-in
  *     for the paper's "KV cache kernel", Sec. 4.2.3),
  *   - the byte-exact block repack between two views (this build's replacement
@@ -232,6 +234,50 @@ int oracle_paged_decode(int32_t Hq, int32_t Hkv, int32_t d, int32_t B0,
                                    ctx_lens, ps, ph, n_pairs, scale, out);
     free(ps); free(ph);
     return rc;
+}
+
+/*
+ * Multi-token (chunked prefill / recompute) causal attention through a view
+ * (Sec. 2.1: a prefill step attends over the prompt with a causal mask; Sec.
+ * 5.2.2: Soft Preempt recomputes the KV of taken-over requests, which is such a
+ * step; Sec. 3: chunked prefill is preserved).  Sequence s has ctx_lens[s]
+ * tokens in the cache, the last q_len[s] = q_off[s+1] - q_off[s] of which are
+ * the new ones: query j of the sequence sits at position
+ * pos = ctx_lens[s] - q_len[s] + j and attends to tokens 0..pos.
+ * q: [total_q][Hql][d] bf16 bits, sequence s owning rows [q_off[s], q_off[s+1]).
+ * Rows are selected by (row index into q, local head); out: [n_rows][d] fp64.
+ * Each row is, by definition, single-query attention over the first pos + 1
+ * tokens: computed as exactly that.
+ */
+int oracle_paged_prefill_rows(int32_t Hq, int32_t Hkv, int32_t d, int32_t B0,
+                              int32_t layout, int32_t p, int32_t r,
+                              const uint16_t* q, const uint16_t* pool,
+                              const int32_t* table, int64_t table_stride,
+                              const int32_t* ctx_lens, const int64_t* q_off, int32_t batch,
+                              const int64_t* row_q, const int32_t* row_head, int64_t n_rows,
+                              double scale, double* out)
+{
+    oracle_view v;
+    int rc = oracle_view_resolve(Hq, Hkv, d, B0, layout, p, r, &v);
+    if (rc) return rc;
+    const int G = Hq / Hkv;
+    const double sc = resolve_scale(scale, d);
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < n_rows; ++k) {
+        const int64_t row = row_q[k];
+        const int i = row_head[k];
+        int s = -1;
+        for (int c = 0; c < batch; ++c)
+            if (row >= q_off[c] && row < q_off[c + 1]) s = c;
+        if (s < 0 || i < 0 || i >= v.Hql) { bad = 1; continue; }
+        const int64_t q_len = q_off[s + 1] - q_off[s];
+        const int64_t pos = (int64_t)ctx_lens[s] - q_len + (row - q_off[s]);
+        if (pos < 0) { bad = 1; continue; }
+        decode_row(&v, q + (row * v.Hql + i) * d, pool, table + (int64_t)s * table_stride,
+                   0, pos + 1, i / G, sc, out + k * d, NULL);
+    }
+    return bad ? ORACLE_EINVAL : ORACLE_OK;
 }
 
 /*

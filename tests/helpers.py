@@ -120,6 +120,71 @@ def make_mixed_case(w: wl.Workload, triples, view_ids, ctx, slack: float = 1.3) 
                      q_slice(q_full, infos[0], views[0].rank), table, pool)
 
 
+@dataclass
+class PrefillCase:
+    w: wl.Workload
+    view: oracle.View
+    info: dict
+    ctx: np.ndarray          # int32[batch] tokens in the cache (the new ones included)
+    q_lens: np.ndarray       # int32[batch] new tokens = last q_lens[s] of the ctx[s]
+    q_off: np.ndarray        # int64[batch+1]
+    seq_off: np.ndarray
+    K: np.ndarray
+    V: np.ndarray
+    q_full: np.ndarray       # uint16[total_q][Hq][d]
+    q: np.ndarray            # uint16[total_q][Hql][d]
+    table: np.ndarray
+    pool: np.ndarray
+
+
+def make_prefill_case(w: wl.Workload, view_triple, ctx, q_lens, slack: float = 1.2) -> PrefillCase:
+    """Cached K/V for ctx[s] tokens per sequence (scattered through the view into a NaN-poisoned
+    pool) and q_lens[s] <= ctx[s] query tokens per sequence, all bf16 N(0,1), seeded."""
+    geom = geometry(w)
+    view = oracle.View(geom, *view_triple)
+    info = view.query()
+    ctx = np.asarray(ctx, dtype=np.int32)
+    q_lens = np.asarray(q_lens, dtype=np.int32)
+    assert (q_lens <= ctx).all() and (q_lens >= 0).all()
+    w_eff = wl.Workload(w.name, w.index, w.n_q_heads, w.n_kv_heads, w.head_dim, w.base_block_size,
+                        len(ctx), w.lengths, w.views)
+    K, V = wl.logical_kv(w_eff, ctx)
+    q_off = wl.seq_offsets(q_lens)
+    q_full = wl.randn_bf16((int(q_off[-1]), w.n_q_heads, w.head_dim), wl.generator(w.index, wl.SUB_QUERY))
+    need = int(wl.blocks_needed(ctx, info["block_tokens"]).sum())
+    perm = wl.shuffled_pool(max(need, 1), slack, wl.generator(w.index, wl.SUB_PERM))
+    table, _ = wl.assign_blocks(ctx, info["block_tokens"], perm)
+    pool = wl.poisoned_pool(len(perm), info["block_bytes"] // 2)
+    seq_off = wl.seq_offsets(ctx)
+    oracle.scatter(view, pool, table, ctx, seq_off, K, V)
+    return PrefillCase(w_eff, view, info, ctx, q_lens, q_off, seq_off, K, V, q_full,
+                       q_slice(q_full, info, view.rank), table, pool)
+
+
+def textbook_causal_attention(c: PrefillCase, scale: float) -> np.ndarray:
+    """softmax(mask(scale * Q K^T)) V per sequence and head with numpy matrix products, fp64, on
+    the logical tensors: Q rows are the sequence's last q_len tokens, the mask keeps key t for the
+    query at position pos iff t <= pos.  out[total_q][Hq][d]."""
+    hq, hkv, d = c.w.n_q_heads, c.w.n_kv_heads, c.w.head_dim
+    G = hq // hkv
+    qf, Kf, Vf = bf16_bits_to_f64(c.q_full), bf16_bits_to_f64(c.K), bf16_bits_to_f64(c.V)
+    out = np.zeros((int(c.q_off[-1]), hq, d))
+    for s in range(len(c.ctx)):
+        n, m = int(c.ctx[s]), int(c.q_lens[s])
+        if m == 0:
+            continue
+        a, qa = int(c.seq_off[s]), int(c.q_off[s])
+        pos = np.arange(n - m, n)[:, None]
+        keep = np.arange(n)[None, :] <= pos
+        for h in range(hq):
+            S = (qf[qa:qa + m, h, :] @ Kf[a:a + n, h // G, :].T) * scale
+            S = np.where(keep, S, -np.inf)
+            P = np.exp(S - S.max(axis=1, keepdims=True))
+            P /= P.sum(axis=1, keepdims=True)
+            out[qa:qa + m, h, :] = P @ Vf[a:a + n, h // G, :]
+    return out
+
+
 def textbook_attention(q_full: np.ndarray, K: np.ndarray, V: np.ndarray, seq_off: np.ndarray,
                        n_q_heads: int, n_kv_heads: int, scale: float) -> np.ndarray:
     """softmax(scale * q K^T) V per sequence and head with numpy matmuls, fp64.
