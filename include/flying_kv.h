@@ -158,6 +158,29 @@ int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * paged_prefill_attn -- causal attention from several new tokens per sequence to everything
+ * cached up to each of them, through a view: one chunk of a prefill (Sec. 2.1; chunked prefill
+ * is kept, Sec. 3) or the recompute step of Soft Preempt (Sec. 5.2.2).  The new tokens' K and V
+ * are already in the pool (kv_append).  Sequence s has ctx_lens[s] cached tokens, the last
+ * q_len[s] = q_offsets[s + 1] - q_offsets[s] of which are the new ones; for its j-th new token,
+ * at position pos = ctx_lens[s] - q_len[s] + j, and local query head i:
+ *     out[q_offsets[s] + j][i][:] = sum_{t <= pos} softmax_t(scale * q[..][i] . K[s][t][i / G]) V[s][t][i / G]
+ *
+ *   q, out       device, bf16 [total_q][n_q_local][head_dim], total_q = q_offsets[batch]
+ *   q_offsets    device, int32 [batch + 1], non-decreasing, q_offsets[0] = 0
+ *   ctx_lens     device, int32 [batch]; q_len[s] <= ctx_lens[s] <= max_ctx_len is a precondition
+ *   max_q_len    host upper bound of q_len (sizes the launch)
+ * Other arguments as paged_decode_attn; no workspace is needed.  q_len[s] = 1 for every s is
+ * paged_decode_attn.  Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, max_q_len >
+ * max_ctx_len, block_table_stride too small), KV_ERR_UNSUPPORTED (head_dim != 128, group size
+ * not a power of two <= 16, block capacity not a multiple of 16), KV_ERR_HIP.
+ */
+int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
+                       const int32_t* block_table, int64_t block_table_stride,
+                       const int32_t* ctx_lens, const int32_t* q_offsets, int batch, int max_ctx_len,
+                       int max_q_len, const kv_view* view, float scale, void* hip_stream);
+
+/*
  * kv_repack -- move KV rows between two arrangements inside one pool, bit-exactly.  This
  * is what a DP->TP or TP->DP transition needs when the existing blocks cannot simply be
  * re-interpreted (the paper's Soft Preempt recomputes the cache instead, Sec. 5.2.2; a
@@ -223,7 +246,8 @@ int64_t kv_get_option(const char* key);
  *       clears them.  which: 0 = decode main kernel, 1 = decode merge kernel, 2 = repack kernel.
  * Not thread-safe; at most 4096 launches per kernel are kept between reads.
  */
-enum { KV_PROF_DECODE_MAIN = 0, KV_PROF_DECODE_MERGE = 1, KV_PROF_REPACK = 2, KV_PROF_KINDS = 3 };
+enum { KV_PROF_DECODE_MAIN = 0, KV_PROF_DECODE_MERGE = 1, KV_PROF_REPACK = 2, KV_PROF_PREFILL = 3,
+       KV_PROF_KINDS = 4 };
 int kv_profile_enable(int on);
 int kv_profile_read(int which, double* total_ms, int64_t* n_launches);
 

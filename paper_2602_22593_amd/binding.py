@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
                                     vp, C.c_size_t, vp]
     L.paged_decode_attn_mixed.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, vp, C.c_int,
                                           C.c_float, vp, C.c_size_t, vp]
+    L.paged_prefill_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, C.c_int, vp,
+                                     C.c_float, vp]
     L.kv_repack.argtypes = [vp, i64, vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp]
     L.kv_append.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp, C.c_int, vp]
     L.kv_validate_tables.argtypes = [vp, i64, vp, i64, vp, C.c_int, vp, vp, i64, vp]
@@ -214,6 +216,34 @@ def paged_decode_attn_mixed(q: torch.Tensor, kv_pool: torch.Tensor, block_table:
     return out
 
 
+def paged_prefill_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch.Tensor,
+                       ctx_lens: torch.Tensor, q_offsets: torch.Tensor, view: KVView, max_ctx_len: int,
+                       max_q_len: int, out: Optional[torch.Tensor] = None, scale: float = 0.0,
+                       stream=None) -> torch.Tensor:
+    """Causal attention of each sequence's last q_len tokens over its cached tokens, through ``view``.
+
+    q: bf16 [total_q][n_q_local][head_dim]; q_offsets: int32 [batch + 1] (device); the K/V of the
+    new tokens are already in the pool.  ``max_ctx_len`` / ``max_q_len`` are host-side bounds.
+    """
+    batch = int(ctx_lens.shape[0])
+    if q.dim() != 3 or tuple(q.shape[1:]) != (view.n_q_local, view.head_dim):
+        raise ValueError(f"q has shape {tuple(q.shape)}, expected [total_q, {view.n_q_local}, {view.head_dim}]")
+    if q_offsets.shape[0] != batch + 1:
+        raise ValueError("q_offsets must be [batch + 1]")
+    if out is None:
+        out = torch.empty_like(q)
+    if block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError("block_table must be [batch][max_blocks]")
+    n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // view.block_bytes
+    rc = lib().paged_prefill_attn(
+        _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"), n_pool_blocks,
+        _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
+        _dev(ctx_lens, (torch.int32,), "ctx_lens"), _dev(q_offsets, (torch.int32,), "q_offsets"), batch,
+        int(max_ctx_len), int(max_q_len), view.handle, float(scale), _stream_ptr(stream))
+    _check(rc, "paged_prefill_attn")
+    return out
+
+
 def kv_repack(kv_pool: torch.Tensor, src_view: KVView, dst_view: KVView,
               src_block_table: torch.Tensor, dst_block_table: torch.Tensor,
               n_tokens: torch.Tensor, max_tokens: int, stream=None) -> None:
@@ -264,7 +294,7 @@ def kv_get_option(key: str) -> int:
     return int(lib().kv_get_option(key.encode()))
 
 
-KV_PROF_DECODE_MAIN, KV_PROF_DECODE_MERGE, KV_PROF_REPACK = 0, 1, 2
+KV_PROF_DECODE_MAIN, KV_PROF_DECODE_MERGE, KV_PROF_REPACK, KV_PROF_PREFILL = 0, 1, 2, 3
 
 
 def kv_profile_enable(on: bool) -> None:

@@ -1,0 +1,302 @@
+// Multi-token causal attention over the paged KV pool, through a layout view: a chunk of a
+// prefill, or the recompute step of Soft Preempt (Sec. 5.2.2 of the paper), both of which
+// attend from several new tokens of a sequence to everything cached up to each of them.
+//
+// A workgroup of four wavefronts owns, for one (sequence, local KV head), a tile of query rows:
+// 64 R rows = (64 R / G) consecutive new tokens x the G query heads that share the KV head; each
+// wavefront holds R blocks of 16 rows.  The workgroup walks the cached tokens in tiles of 32,
+// staging each K and V tile once in LDS (double buffered, fetched with 16-byte loads by all 256
+// lanes while the previous tile is being consumed); each wavefront then takes its MFMA operands
+// from LDS and re-uses every K / V operand for its R row blocks.
+//
+// Per tile and row block, lane l = (c = l % 16, quad = l / 16), exactly as in the decode kernel:
+//   S^T[token][c] = K[token][:] . q[c][:]     A operand = K rows from LDS (token 16 h + 4 (r % 4)
+//                                             + r / 4 in A row r of half h), B operand = q
+//   O^T[e][c]     = sum_t V[t][e] P[c][t]     A operand = V^T, built in the lane from 16-byte
+//                                             pieces of V rows with byte permutes
+// so the accumulator layout of S^T is already the B layout of the second product and only the
+// running maximum crosses lanes.  Column c of row block b of wavefront w is row
+// rho = (w R + b) 16 + c of the tile: token rho / G, head rho % G.  The causal mask keeps
+// token t for a query at position pos iff t <= pos; since pos < ctx_len it also masks the slots
+// past the end of the sequence.
+#include "decode_common.h"
+
+using namespace kvdec;
+
+namespace {
+
+constexpr int D = 128;
+constexpr int kThreads = 256;
+
+struct prefill_args {
+    const uint16_t* q;      // [total_q][n_q_local][128]
+    uint16_t* out;
+    const uint16_t* pool;
+    const int32_t* table;
+    int64_t table_stride;
+    const int32_t* ctx_lens;
+    const int32_t* q_off;   // [batch + 1]
+    kv_view_dev v;
+    float scale_log2e;
+    int32_t group;          // G in {1, 2, 4, 8, 16}
+    int32_t group_shift;
+};
+
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+template <int R>
+__global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefill_args a)
+{
+    // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)), V pieces plain
+    __shared__ kv_u32x4 s_k[2][512];
+    __shared__ kv_u32x4 s_v[2][512];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int r = lane & 15, quad = lane >> 4;
+    const kv_view_dev& v = a.v;
+    const int G = a.group;
+    const int s = blockIdx.z, hl = blockIdx.y;
+    const int tokens_per_wg = (64 * R) >> a.group_shift;
+
+    const int n = a.ctx_lens[s];
+    const int q0 = a.q_off[s];
+    const int q_len = a.q_off[s + 1] - q0;
+    // longest tiles first: the last query tile of a sequence sees the most keys
+    const int j0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * tokens_per_wg;
+    if (j0 >= q_len || n <= 0) return;
+    const int first_pos = n - q_len;                         // position of the sequence's query 0
+    const int j_last = min(j0 + tokens_per_wg, q_len) - 1;   // last query token of this tile
+    const int n_tiles = ((first_pos + j_last) >> 5) + 1;     // key tiles 0 .. n_tiles - 1
+
+    // ---- this lane's query rows (B operands), one per row block --------------------------------
+    bf16x8 qb[R][4];
+    int pos[R];       // position of the column's query token
+    int64_t orow[R];  // element offset of the column's output row, or -1 if the column is padding
+#pragma unroll
+    for (int b = 0; b < R; ++b) {
+        const int rho = (wave * R + b) * 16 + r;
+        const int jt = j0 + (rho >> a.group_shift), g = rho & (G - 1);
+        const int jc = min(jt, q_len - 1);
+        pos[b] = first_pos + jc;
+        const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + g) * D;
+        orow[b] = jt < q_len ? row : -1;
+        const char* qrow = reinterpret_cast<const char*>(a.q + row) + quad * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qb[b][kk] = as_bf16x8(*reinterpret_cast<const kv_u32x4*>(qrow + kk * 64));
+    }
+    // keys below this position need no mask for any column of the wavefront
+    int min_pos = pos[0];
+#pragma unroll
+    for (int b = 1; b < R; ++b) min_pos = min(min_pos, pos[b]);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) min_pos = min(min_pos, __shfl_xor(min_pos, off));
+    min_pos = uniform(min_pos);
+    int max_pos = pos[R - 1];
+    max_pos = uniform(__shfl(max_pos, 15));  // rows ascend with the column: the last is the largest
+
+    // ---- staging: lane tau fetches piece tau % 16 of rows tau / 16 and 16 + tau / 16 of a tile --
+    const int ld_row = tid >> 4, ld_c = tid & 15;
+    const int token_stride_bytes = v.token_stride * 2;
+    const int64_t plane_bytes = v.plane_elems * 2;
+    const int halves_per_block = v.block_tokens >> 4;
+    const int half_shift = v.block_shift >= 4 ? v.block_shift - 4 : -1;
+    const int last_half = (n - 1) >> 4;
+    typedef const __attribute__((address_space(4))) int32_t* const_ids;
+    const const_ids ids = (const_ids)(a.table + (int64_t)s * a.table_stride);
+    const char* head_base = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D) + ld_c * 16;
+
+    // address of this lane's piece of key row (tile, half h): rows past the end of the sequence
+    // are replaced by its last token (finite data, masked later)
+    auto piece = [&](int tile, int h) -> const char* {
+        const int hh = min(2 * tile + h, last_half);
+        const int hb = half_shift >= 0 ? (hh >> half_shift) : hh / halves_per_block;
+        const int blk = ids[hb];
+        const int tok = min(32 * tile + 16 * h + ld_row, n - 1);
+        const int slot = tok - hb * v.block_tokens;
+        return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot * token_stride_bytes;
+    };
+    kv_u32x4 stage_k[2], stage_v[2];
+    auto fetch = [&](int tile) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const char* p = piece(tile, h);
+            stage_k[h] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(p));
+            stage_v[h] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(p + plane_bytes));
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int row = 16 * h + ld_row;
+            s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[h];
+            s_v[buf][row * 16 + ld_c] = stage_v[h];
+        }
+    };
+
+    float m[R], l[R];
+    f32x4 o[R][8];  // o[b][j][i] = O[column][32 quad + 8 i + j]
+#pragma unroll
+    for (int b = 0; b < R; ++b) {
+        m[b] = kNegInf;
+        l[b] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    const int k_row = 4 * (r & 3) + (r >> 2);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int buf = tile & 1;
+        if (tile + 1 < n_tiles) fetch(tile + 1);
+
+        const int base = 32 * tile;
+        if (base <= max_pos) {  // else every key of the tile lies after all of this wavefront's queries
+            // ---- S^T = K q^T ------------------------------------------------------------------------
+            f32x4 sacc[R][2];
+#pragma unroll
+            for (int b = 0; b < R; ++b) sacc[b][0] = sacc[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const kv_u32x4 ka = s_k[buf][(16 * h + k_row) * 16 + ((4 * kk + quad) ^ k_row)];
+#pragma unroll
+                    for (int b = 0; b < R; ++b)
+                        sacc[b][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka), qb[b][kk],
+                                                                            sacc[b][h], 0, 0, 0);
+                }
+            // ---- online softmax per column ------------------------------------------------------------
+            const bool masked = base + 31 > min_pos;
+            bf16x8 pb[R];
+#pragma unroll
+            for (int b = 0; b < R; ++b) {
+                float sv[8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float x = sacc[b][h][i] * a.scale_log2e;
+                        if (masked) x = (base + 16 * h + 4 * i + quad <= pos[b]) ? x : kNegInf;
+                        sv[4 * h + i] = x;
+                    }
+                float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                                 fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // tile 0 holds key 0, which every query sees: the maximum is finite from then on
+                const float m_new = fmaxf(m[b], mx);
+                if (__builtin_amdgcn_ballot_w64(m_new != m[b]) != 0) {
+                    const float alpha = fast_exp2(m[b] - m_new);
+                    l[b] *= alpha;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[b][j] *= alpha;
+                    m[b] = m_new;
+                }
+                float p[8], psum = 0.f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    p[u] = fast_exp2(sv[u] - m_new);
+                    psum += p[u];
+                }
+                l[b] += psum;
+                pb[b] = as_bf16x8(kv_u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
+                                           pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])});
+            }
+            // ---- O^T += V^T P^T --------------------------------------------------------------------------
+            kv_u32x4 vr[8];  // piece r of token 16 h + 4 i + quad
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vr[4 * h + i] = s_v[buf][(16 * h + 4 * i + quad) * 16 + r];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                kv_u32x4 lo, hi;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    lo[u] = __builtin_amdgcn_perm(vr[2 * u + 1][w], vr[2 * u][w], 0x05040100u);
+                    hi[u] = __builtin_amdgcn_perm(vr[2 * u + 1][w], vr[2 * u][w], 0x07060302u);
+                }
+#pragma unroll
+                for (int b = 0; b < R; ++b) {
+                    o[b][2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(lo), pb[b], o[b][2 * w], 0, 0, 0);
+                    o[b][2 * w + 1] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(hi), pb[b], o[b][2 * w + 1], 0, 0, 0);
+                }
+            }
+        }
+
+        if (tile + 1 < n_tiles) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store ------------------------------------------------------------------------
+#pragma unroll
+    for (int b = 0; b < R; ++b) {
+        float lt = l[b];
+        lt += __shfl_xor(lt, 16);
+        lt += __shfl_xor(lt, 32);
+        if (orow[b] >= 0) {
+            const float inv = 1.0f / lt;
+            uint16_t* dst = a.out + orow[b] + 32 * quad;
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                kv_u32x4 pk;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    pk[u] = pack_bf16x2(o[b][2 * u][ii] * inv, o[b][2 * u + 1][ii] * inv);
+                *reinterpret_cast<kv_u32x4*>(dst + 8 * ii) = pk;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
+                                  const int32_t* block_table, int64_t block_table_stride,
+                                  const int32_t* ctx_lens, const int32_t* q_offsets, int batch,
+                                  int max_ctx_len, int max_q_len, const kv_view* view, float scale,
+                                  void* hip_stream)
+{
+    if (!kv_view_ok(view) || batch < 0 || max_ctx_len < 0 || max_q_len < 0 || n_pool_blocks < 0 ||
+        block_table_stride < 0 || max_q_len > max_ctx_len)
+        return KV_ERR_INVALID_ARG;
+    if (batch == 0 || max_q_len == 0) return KV_OK;
+    if (!q || !out || !ctx_lens || !q_offsets || !kv_pool || !block_table) return KV_ERR_INVALID_ARG;
+    const int64_t need_cols = ((int64_t)max_ctx_len + view->block_tokens - 1) / view->block_tokens;
+    if (block_table_stride < need_cols) return KV_ERR_INVALID_ARG;
+    const int G = view->group;
+    if (view->geom.head_dim != D || view->block_tokens % 16 != 0 || G > 16 || (G & (G - 1)) != 0)
+        return KV_ERR_UNSUPPORTED;
+    if (batch > 65535 || view->n_kv_local > 65535) return KV_ERR_UNSUPPORTED;
+    prefill_args a;
+    a.q = (const uint16_t*)q;
+    a.out = (uint16_t*)out;
+    a.pool = (const uint16_t*)kv_pool;
+    a.table = block_table;
+    a.table_stride = block_table_stride;
+    a.ctx_lens = ctx_lens;
+    a.q_off = q_offsets;
+    a.v = kv_view_to_dev(view);
+    a.scale_log2e = (scale > 0.f ? scale : 1.0f / sqrtf((float)D)) * 1.4426950408889634f;
+    a.group = G;
+    a.group_shift = 0;
+    while ((1 << a.group_shift) < G) ++a.group_shift;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int R = (int)kv_option_variant() == 1 ? 4 : 2;
+    const int tokens_per_wg = (64 * R) / G;
+    const dim3 grid((unsigned)((max_q_len + tokens_per_wg - 1) / tokens_per_wg), (unsigned)view->n_kv_local,
+                    (unsigned)batch);
+    int slot = kv_prof_begin(KV_PROF_PREFILL, st);
+    if (R == 4)
+        hipLaunchKernelGGL(prefill_kernel<4>, grid, dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(prefill_kernel<2>, grid, dim3(kThreads), 0, st, a);
+    kv_prof_end(KV_PROF_PREFILL, slot, st);
+    return kv_record_hip_error(hipGetLastError(), "paged_prefill_attn launch");
+}
