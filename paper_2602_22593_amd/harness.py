@@ -104,6 +104,48 @@ def build_decode_case(w: wl.Workload, triple, device="cuda:0", n_copies: int = 1
 
 
 @dataclass
+class PrefillCase:
+    view: kv.KVView
+    ctx: np.ndarray
+    q_lens: np.ndarray
+    q: torch.Tensor
+    out: torch.Tensor
+    pool: torch.Tensor
+    table_dev: torch.Tensor
+    ctx_dev: torch.Tensor
+    q_off_dev: torch.Tensor
+    flops: float                    # 4 * head_dim * n_q_local * (unmasked query-key pairs)
+    kv_bytes: int                   # K and V of the cached tokens, read once
+
+    def run(self, i: int = 0) -> None:
+        kv.paged_prefill_attn(self.q, self.pool, self.table_dev, self.ctx_dev, self.q_off_dev, self.view,
+                              int(self.ctx.max()), int(self.q_lens.max()), out=self.out)
+
+
+def build_prefill_case(w: wl.Workload, triple, ctx, q_lens, device="cuda:0", slack: float = 1.2) -> PrefillCase:
+    """Sequences with ctx[s] cached tokens of which the last q_lens[s] are queried; random pool,
+    shuffled block table, bf16 N(0,1) queries (timing recipe)."""
+    view = make_view(w, triple)
+    ctx = np.asarray(ctx, dtype=np.int32)
+    q_lens = np.asarray(q_lens, dtype=np.int32)
+    need = int(wl.blocks_needed(ctx, view.block_tokens).sum())
+    perm = wl.shuffled_pool(need, slack, wl.generator(w.index, wl.SUB_PERM + 300))
+    table, _ = wl.assign_blocks(ctx, view.block_tokens, perm)
+    pool = random_pool(len(perm), view.block_bytes // 2, wl.SEED_BASE + 10 * w.index + wl.SUB_DATA + 3000, device)
+    q_off = wl.seq_offsets(q_lens)
+    g = torch.Generator(device=device)
+    g.manual_seed(wl.SEED_BASE + 10 * w.index + wl.SUB_QUERY + 3000)
+    q = torch.randn((int(q_off[-1]), view.n_q_local, view.head_dim), generator=g, device=device,
+                    dtype=torch.float32).to(torch.bfloat16)
+    n, m = ctx.astype(np.float64), q_lens.astype(np.float64)
+    pairs = float((m * (n - m) + m * (m + 1) / 2).sum())
+    return PrefillCase(view, ctx, q_lens, q, torch.empty_like(q), pool, torch.from_numpy(table).to(device),
+                       torch.from_numpy(ctx).to(device), torch.from_numpy(q_off.astype(np.int32)).to(device),
+                       4.0 * view.head_dim * view.n_q_local * pairs,
+                       int(ctx.astype(np.int64).sum()) * view.n_kv_local * view.head_dim * 2 * 2)
+
+
+@dataclass
 class RepackCase:
     workload: wl.Workload
     src_view: kv.KVView
