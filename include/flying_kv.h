@@ -181,6 +181,47 @@ int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_
                        int max_q_len, const kv_view* view, float scale, void* hip_stream);
 
 /*
+ * Weight shard views (Model Weights Manager, Sec. 4.1; Eq. 1: W_active^(r) = View(W_full, dim, r,
+ * m)).  A weight is stored once, whole, as bf16 [out_features][in_features] row-major; a view
+ * names the stored rows (up to three contiguous segments, concatenated) and the contiguous range
+ * of stored columns that are active for rank r of an m-way TP group.  Plain host data: the
+ * caller owns it, nothing on the device is touched or copied.
+ */
+typedef struct kv_weight_view {
+    int32_t n_segments;      /* 1..3 */
+    int64_t row_start[3];    /* first stored row of each segment */
+    int64_t row_count[3];
+    int64_t col_start;
+    int64_t col_count;
+} kv_weight_view;
+
+/* The r-th of m equal parts along dim (0: stored rows = output features, the column-parallel
+ * layer of Sec. 4.1.1; 1: stored columns = input features, the row-parallel layer).
+ * KV_ERR_INVALID_ARG if r is not in [0, m) or the dimension is not divisible by m. */
+int kv_weight_view_make(int dim, int r, int m, int64_t n_rows, int64_t n_cols, kv_weight_view* out);
+
+/* Rank r's slice of a fused QKV weight [(n_q_heads + 2 n_kv_heads) * head_dim][hidden] (query
+ * heads, then key heads, then value heads): three row segments holding the rank's contiguous
+ * head range of each part (Sec. 4.1.1).  KV_ERR_INVALID_ARG if m does not divide the head counts. */
+int kv_weight_view_fused_qkv(const kv_geometry* g, int64_t hidden, int r, int m, kv_weight_view* out);
+
+/*
+ * kv_linear_view -- y = x W_active^T on the view, reading the full weight in place.
+ *   x       device, bf16 [M][view->col_count], row stride ldx elements          (read)
+ *   w_full  device, bf16 [w_rows][ldw]: the whole stored weight, ldw its row length (read)
+ *   y       device, bf16 [M][sum of row_count], row stride ldy elements          (written)
+ * fp32 accumulation, one rounding to bf16 at the end.  For the row-parallel layer y is the
+ * rank's partial sum (the all-reduce over ranks is the caller's).  Tuned for decode batches (M up
+ * to a few hundred); any M is accepted.
+ * Errors: KV_ERR_INVALID_ARG (null pointers, view outside the weight, strides too small),
+ * KV_ERR_UNSUPPORTED (col_count not a multiple of 128, a row segment not a multiple of 32,
+ * col_start / ldx / ldw not multiples of 8 elements, ldy not a multiple of 4, pointers not
+ * 16-byte aligned), KV_ERR_HIP.
+ */
+int kv_linear_view(const void* x, int64_t ldx, const void* w_full, int64_t w_rows, int64_t ldw,
+                   const kv_weight_view* view, void* y, int64_t ldy, int M, void* hip_stream);
+
+/*
  * kv_repack -- move KV rows between two arrangements inside one pool, bit-exactly.  This
  * is what a DP->TP or TP->DP transition needs when the existing blocks cannot simply be
  * re-interpreted (the paper's Soft Preempt recomputes the cache instead, Sec. 5.2.2; a
@@ -247,7 +288,7 @@ int64_t kv_get_option(const char* key);
  * Not thread-safe; at most 4096 launches per kernel are kept between reads.
  */
 enum { KV_PROF_DECODE_MAIN = 0, KV_PROF_DECODE_MERGE = 1, KV_PROF_REPACK = 2, KV_PROF_PREFILL = 3,
-       KV_PROF_KINDS = 4 };
+       KV_PROF_LINEAR = 4, KV_PROF_KINDS = 5 };
 int kv_profile_enable(int on);
 int kv_profile_read(int which, double* total_ms, int64_t* n_launches);
 

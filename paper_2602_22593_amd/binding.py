@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
                                           C.c_float, vp, C.c_size_t, vp]
     L.paged_prefill_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, C.c_int, vp,
                                      C.c_float, vp]
+    L.kv_weight_view_make.argtypes = [C.c_int, C.c_int, C.c_int, i64, i64, vp]
+    L.kv_weight_view_fused_qkv.argtypes = [vp, i64, C.c_int, C.c_int, vp]
+    L.kv_linear_view.argtypes = [vp, i64, vp, i64, i64, vp, vp, i64, C.c_int, vp]
     L.kv_repack.argtypes = [vp, i64, vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp]
     L.kv_append.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp, C.c_int, vp]
     L.kv_validate_tables.argtypes = [vp, i64, vp, i64, vp, C.c_int, vp, vp, i64, vp]
@@ -134,6 +137,17 @@ def _dev(t: torch.Tensor, dtypes, name: str) -> C.c_void_p:
         raise ValueError(f"{name} has dtype {t.dtype}, expected one of {dtypes}")
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _dev_rows(t: torch.Tensor, dtypes, name: str) -> C.c_void_p:
+    """A 2-d device tensor whose rows are contiguous (the row stride itself is free)."""
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name} has dtype {t.dtype}, expected one of {dtypes}")
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-d with contiguous rows")
     return C.c_void_p(t.data_ptr())
 
 
@@ -244,6 +258,45 @@ def paged_prefill_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torc
     return out
 
 
+class kv_weight_view(C.Structure):
+    """Mirror of the C struct: stored rows (up to three segments) and columns that are active."""
+    _fields_ = [("n_segments", C.c_int32), ("row_start", C.c_int64 * 3), ("row_count", C.c_int64 * 3),
+                ("col_start", C.c_int64), ("col_count", C.c_int64)]
+
+    @property
+    def n_rows(self) -> int:
+        return sum(self.row_count[i] for i in range(self.n_segments))
+
+
+def kv_weight_view_make(dim: int, r: int, m: int, n_rows: int, n_cols: int) -> kv_weight_view:
+    v = kv_weight_view()
+    _check(lib().kv_weight_view_make(dim, r, m, n_rows, n_cols, C.byref(v)), "kv_weight_view_make")
+    return v
+
+
+def kv_weight_view_fused_qkv(n_q_heads: int, n_kv_heads: int, head_dim: int, hidden: int, r: int,
+                             m: int) -> kv_weight_view:
+    g = kv_geometry(n_q_heads, n_kv_heads, head_dim, 16, 0)
+    v = kv_weight_view()
+    _check(lib().kv_weight_view_fused_qkv(C.byref(g), hidden, r, m, C.byref(v)), "kv_weight_view_fused_qkv")
+    return v
+
+
+def kv_linear_view(x: torch.Tensor, w_full: torch.Tensor, view: kv_weight_view,
+                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """y[M][view rows] (bf16) = x @ W_active^T, W_active = ``view`` of the stored ``w_full`` [out][in]."""
+    if x.dim() != 2 or w_full.dim() != 2 or x.shape[1] != view.col_count:
+        raise ValueError("x must be [M][view.col_count], w_full [out][in]")
+    M = int(x.shape[0])
+    if out is None:
+        out = torch.empty((M, view.n_rows), dtype=torch.bfloat16, device=x.device)
+    rc = lib().kv_linear_view(_dev_rows(x, _BF16, "x"), x.stride(0), _dev_rows(w_full, _BF16, "w_full"),
+                              int(w_full.shape[0]), w_full.stride(0), C.byref(view),
+                              _dev_rows(out, _BF16, "out"), out.stride(0), M, _stream_ptr(stream))
+    _check(rc, "kv_linear_view")
+    return out
+
+
 def kv_repack(kv_pool: torch.Tensor, src_view: KVView, dst_view: KVView,
               src_block_table: torch.Tensor, dst_block_table: torch.Tensor,
               n_tokens: torch.Tensor, max_tokens: int, stream=None) -> None:
@@ -294,7 +347,7 @@ def kv_get_option(key: str) -> int:
     return int(lib().kv_get_option(key.encode()))
 
 
-KV_PROF_DECODE_MAIN, KV_PROF_DECODE_MERGE, KV_PROF_REPACK, KV_PROF_PREFILL = 0, 1, 2, 3
+KV_PROF_DECODE_MAIN, KV_PROF_DECODE_MERGE, KV_PROF_REPACK, KV_PROF_PREFILL, KV_PROF_LINEAR = 0, 1, 2, 3, 4
 
 
 def kv_profile_enable(on: bool) -> None:

@@ -1,0 +1,254 @@
+// Linear layer on a zero-copy shard view of a full weight (Model Weights Manager, Sec. 4.1 of
+// the paper; Eq. 1: W_active^(r) = View(W_full, dim, r, m)): y = x W_active^T, where W_active is
+// a set of stored rows (output features; up to three contiguous segments, as rank r's Q, K and V
+// heads of a fused QKV weight) and a contiguous range of stored columns (input features, for the
+// row-parallel output projection) of a weight kept once, whole, as [out][in] bf16.  Nothing is
+// copied: the kernel addresses the full matrix with its own leading dimension.
+//
+// Shaped for decode batches (M up to a few hundred rows): the weight slice is streamed from HBM
+// once per 64 batch rows and is the dominant traffic; x is small and comes from the caches.
+// A workgroup owns 32 logical weight rows x 64 batch rows; its four wavefronts split the input
+// dimension in slabs of 128 (wavefront w takes slabs w, w + 4, ...), each accumulating
+//   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
+// with 16x16x32 bf16 MFMA (A operand = 16 weight rows, B operand = 16 batch rows; both are read
+// in operand order straight from global memory, 16 bytes per lane), the next slab's operands in
+// flight while the current one is consumed.  The four partial tiles are summed through LDS and
+// stored as bf16.
+#include <string.h>
+
+#include "decode_common.h"
+
+using namespace kvdec;
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowBlocks = 2;   // 16-row blocks of the weight per workgroup
+constexpr int kColBlocks = 4;   // 16-row blocks of x per workgroup
+constexpr int kSlab = 128;      // input features per step
+
+struct linear_args {
+    const uint16_t* x;
+    int64_t ldx;
+    const uint16_t* w;
+    int64_t ldw;
+    uint16_t* y;
+    int64_t ldy;
+    int32_t M, Nl, Kl;
+    int64_t col_start;
+    int32_t n_seg;
+    int64_t seg_start[3];   // first stored row of each segment
+    int32_t seg_first[4];   // first logical row of each segment; seg_first[n_seg] = Nl
+};
+
+struct slab_regs {
+    kv_u32x4 a[kRowBlocks][4];
+    kv_u32x4 b[kColBlocks][4];
+};
+
+__global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
+{
+    __shared__ float s_part[4][kRowBlocks * kColBlocks * 256];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, quad = lane >> 4;
+    const int m0 = blockIdx.x * (16 * kColBlocks);
+    const int n0 = blockIdx.y * (16 * kRowBlocks);
+
+    // the 32 logical rows of this workgroup lie in one segment (segment sizes are multiples of 32)
+    int seg = 0;
+    while (seg + 1 < p.n_seg && n0 >= p.seg_first[seg + 1]) ++seg;
+    const int64_t phys0 = p.seg_start[seg] + (n0 - p.seg_first[seg]);
+
+    const char* wbase[kRowBlocks];
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+        wbase[rb] = reinterpret_cast<const char*>(p.w + (phys0 + 16 * rb + r) * p.ldw + p.col_start) + quad * 16;
+    const char* xbase[kColBlocks];
+#pragma unroll
+    for (int cb = 0; cb < kColBlocks; ++cb) {
+        const int row = min(m0 + 16 * cb + r, p.M - 1);  // rows past M repeat the last one; not stored
+        xbase[cb] = reinterpret_cast<const char*>(p.x + (int64_t)row * p.ldx) + quad * 16;
+    }
+
+    auto fetch = [&](slab_regs& t, int slab) {
+        const int64_t off = (int64_t)slab * (kSlab * 2);
+#pragma unroll
+        for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                t.a[rb][kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase[rb] + off + kk * 64));
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                t.b[cb][kk] = *reinterpret_cast<const kv_u32x4*>(xbase[cb] + off + kk * 64);
+    };
+
+    f32x4 acc[kRowBlocks][kColBlocks];
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto consume = [&](const slab_regs& t) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < kColBlocks; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.a[rb][kk]), as_bf16x8(t.b[cb][kk]),
+                                                                         acc[rb][cb], 0, 0, 0);
+    };
+
+    const int n_slabs = p.Kl / kSlab;
+    int slab = wave;
+    if (slab + 12 < n_slabs) {
+        // steady state without conditional loads: two slabs in flight
+        slab_regs ta, tb;
+        fetch(ta, slab);
+        fetch(tb, slab + 4);
+        do {
+            consume(ta);
+            fetch(ta, slab + 8);
+            consume(tb);
+            fetch(tb, slab + 12);
+            slab += 8;
+        } while (slab + 12 < n_slabs);
+        // slabs `slab` and `slab + 4` are loaded; `slab + 8` may remain
+        consume(ta);
+        if (slab + 8 < n_slabs) fetch(ta, slab + 8);
+        consume(tb);
+        if (slab + 8 < n_slabs) consume(ta);
+    } else {
+        slab_regs ta;
+        for (; slab < n_slabs; slab += 4) {
+            fetch(ta, slab);
+            consume(ta);
+        }
+    }
+
+    // ---- sum the four wavefronts' tiles, convert, store ------------------------------------------
+    // acc[rb][cb][i] = y[m0 + 16 cb + r][n0 + 16 rb + 4 quad + i]
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb)
+            *reinterpret_cast<f32x4*>(&s_part[wave][((rb * kColBlocks + cb) * 64 + lane) * 4]) = acc[rb][cb];
+    __syncthreads();
+    // lane layout of the tile: thread t handles two (rb, cb, lane) records
+#pragma unroll
+    for (int k = 0; k < (kRowBlocks * kColBlocks * 64) / kThreads; ++k) {
+        const int rec = tid + k * kThreads;
+        const f32x4 s = *reinterpret_cast<const f32x4*>(&s_part[0][rec * 4]) +
+                        *reinterpret_cast<const f32x4*>(&s_part[1][rec * 4]) +
+                        *reinterpret_cast<const f32x4*>(&s_part[2][rec * 4]) +
+                        *reinterpret_cast<const f32x4*>(&s_part[3][rec * 4]);
+        const int ln = rec & 63, blk = rec >> 6;
+        const int cb = blk % kColBlocks, rb = blk / kColBlocks;
+        const int m = m0 + 16 * cb + (ln & 15);
+        if (m < p.M) {
+            uint16_t* dst = p.y + (int64_t)m * p.ldy + n0 + 16 * rb + 4 * (ln >> 4);
+            uint2 pk;
+            pk.x = pack_bf16x2(s[0], s[1]);
+            pk.y = pack_bf16x2(s[2], s[3]);
+            *reinterpret_cast<uint2*>(dst) = pk;
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" int kv_weight_view_make(int dim, int r, int m, int64_t n_rows, int64_t n_cols, kv_weight_view* out)
+{
+    if (!out || m < 1 || r < 0 || r >= m || n_rows <= 0 || n_cols <= 0 || (dim != 0 && dim != 1))
+        return KV_ERR_INVALID_ARG;
+    if ((dim == 0 ? n_rows : n_cols) % m != 0) return KV_ERR_INVALID_ARG;
+    memset(out, 0, sizeof(*out));
+    out->n_segments = 1;
+    if (dim == 0) {
+        out->row_start[0] = r * (n_rows / m);
+        out->row_count[0] = n_rows / m;
+        out->col_start = 0;
+        out->col_count = n_cols;
+    } else {
+        out->row_start[0] = 0;
+        out->row_count[0] = n_rows;
+        out->col_start = r * (n_cols / m);
+        out->col_count = n_cols / m;
+    }
+    return KV_OK;
+}
+
+extern "C" int kv_weight_view_fused_qkv(const kv_geometry* g, int64_t hidden, int r, int m, kv_weight_view* out)
+{
+    if (!g || !out || m < 1 || r < 0 || r >= m || hidden <= 0 || g->n_q_heads <= 0 || g->n_kv_heads <= 0 ||
+        g->head_dim <= 0 || g->n_q_heads % m != 0 || g->n_kv_heads % m != 0)
+        return KV_ERR_INVALID_ARG;
+    const int64_t d = g->head_dim, hq = g->n_q_heads / m, hkv = g->n_kv_heads / m;
+    memset(out, 0, sizeof(*out));
+    out->n_segments = 3;
+    out->row_start[0] = r * hq * d;
+    out->row_count[0] = hq * d;
+    out->row_start[1] = (int64_t)g->n_q_heads * d + r * hkv * d;
+    out->row_count[1] = hkv * d;
+    out->row_start[2] = (int64_t)(g->n_q_heads + g->n_kv_heads) * d + r * hkv * d;
+    out->row_count[2] = hkv * d;
+    out->col_start = 0;
+    out->col_count = hidden;
+    return KV_OK;
+}
+
+extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, int64_t w_rows, int64_t ldw,
+                              const kv_weight_view* view, void* y, int64_t ldy, int M, void* hip_stream)
+{
+    if (!view || M < 0 || view->n_segments < 1 || view->n_segments > 3 || w_rows <= 0 || ldw <= 0)
+        return KV_ERR_INVALID_ARG;
+    int64_t n_l = 0;
+    for (int i = 0; i < view->n_segments; ++i) {
+        if (view->row_start[i] < 0 || view->row_count[i] <= 0 || view->row_start[i] + view->row_count[i] > w_rows)
+            return KV_ERR_INVALID_ARG;
+        n_l += view->row_count[i];
+    }
+    if (view->col_start < 0 || view->col_count <= 0 || view->col_start + view->col_count > ldw ||
+        ldx < view->col_count || ldy < n_l)
+        return KV_ERR_INVALID_ARG;
+    if (M == 0) return KV_OK;
+    if (!x || !w_full || !y) return KV_ERR_INVALID_ARG;
+    // 16-byte operand loads, whole 128-wide slabs, 32-row workgroup tiles inside one segment
+    if (view->col_count % kSlab != 0 || view->col_start % 8 != 0 || ldx % 8 != 0 || ldw % 8 != 0 || ldy % 4 != 0 ||
+        ((uintptr_t)x & 15) || ((uintptr_t)w_full & 15) || ((uintptr_t)y & 7) || n_l > 0x7fffffff ||
+        view->col_count > 0x7fffffff)
+        return KV_ERR_UNSUPPORTED;
+    for (int i = 0; i < view->n_segments; ++i)
+        if (view->row_count[i] % (16 * kRowBlocks) != 0) return KV_ERR_UNSUPPORTED;
+    linear_args p;
+    p.x = (const uint16_t*)x;
+    p.ldx = ldx;
+    p.w = (const uint16_t*)w_full;
+    p.ldw = ldw;
+    p.y = (uint16_t*)y;
+    p.ldy = ldy;
+    p.M = M;
+    p.Nl = (int32_t)n_l;
+    p.Kl = (int32_t)view->col_count;
+    p.col_start = view->col_start;
+    p.n_seg = view->n_segments;
+    int32_t first = 0;
+    for (int i = 0; i < 3; ++i) {
+        p.seg_start[i] = i < view->n_segments ? view->row_start[i] : 0;
+        p.seg_first[i] = first;
+        if (i < view->n_segments) first += (int32_t)view->row_count[i];
+    }
+    p.seg_first[3] = first;
+    for (int i = view->n_segments; i < 4; ++i) p.seg_first[i] = first;
+    const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
+    const int64_t n_tiles = n_l / (16 * kRowBlocks);
+    if (m_tiles > 0x7fffffff || n_tiles > 65535) return KV_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int slot = kv_prof_begin(KV_PROF_LINEAR, st);
+    hipLaunchKernelGGL(linear_view_kernel, dim3((unsigned)m_tiles, (unsigned)n_tiles), dim3(kThreads), 0, st, p);
+    kv_prof_end(KV_PROF_LINEAR, slot, st);
+    return kv_record_hip_error(hipGetLastError(), "kv_linear_view launch");
+}

@@ -1,0 +1,110 @@
+"""GPU parity of kv_linear_view (linear layer on a zero-copy weight shard view) with the oracle."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import weights as ow
+from paper_2602_22593_amd import binding as kv
+from paper_2602_22593_amd import workloads as wl
+
+from helpers import bf16_bits_to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bits(shape, seed):
+    return wl.randn_bf16(shape, wl.generator(41, seed))
+
+
+def dev(a):
+    return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def check(got_bits, want, K, what):
+    """fp32 accumulation of K products of N(0,1) values, one rounding to bf16 at the end: the
+    result differs from the fp64 value by at most half a bf16 ulp of it (2^-9 relative) plus the
+    accumulation error, K * 2^-24 * sum |x w| <~ K * 2^-24 * K; allow 2^-8 relative and that
+    absolute term (doubled)."""
+    got = bf16_bits_to_f64(got_bits)
+    assert np.isfinite(got).all(), what
+    tol = np.abs(want) * 2.0 ** -8 + 2.0 * K * K * 2.0 ** -24 + 1e-6
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, worst {np.abs(got - want).max():.4g}"
+
+
+def gpu_view(o: ow.WeightView) -> kv.kv_weight_view:
+    v = kv.kv_weight_view()
+    v.n_segments = len(o.row_segments)
+    for i, (a, c) in enumerate(o.row_segments):
+        v.row_start[i], v.row_count[i] = a, c
+    v.col_start, v.col_count = o.col_start, o.col_count
+    return v
+
+
+@pytest.mark.parametrize("M", [1, 17, 64, 100, 256])
+@pytest.mark.parametrize("m,r", [(1, 0), (2, 1), (8, 5)])
+def test_fused_qkv_column_slice(M, m, r):
+    """Llama-8B-shaped heads on a narrow hidden size (oracle cost): rank r's Q, K and V rows of the
+    fused weight, batch sizes inside, at and past the 64-row tile."""
+    hq, hkv, d, hidden = 32, 8, 128, 512
+    x, w = bits((M, hidden), 10 + M), bits(((hq + 2 * hkv) * d, hidden), 20)
+    ov = ow.weight_view_fused_qkv(hq, hkv, d, hidden, r, m)
+    gv = kv.kv_weight_view_fused_qkv(hq, hkv, d, hidden, r, m)
+    assert [(gv.row_start[i], gv.row_count[i]) for i in range(3)] == list(ov.row_segments)
+    y = kv.kv_linear_view(dev(x), dev(w), gv)
+    torch.cuda.synchronize()
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), ow.linear_view(x, w, ov), hidden, f"qkv M={M} {r}/{m}")
+
+
+@pytest.mark.parametrize("M", [3, 64, 130])
+@pytest.mark.parametrize("m,r", [(1, 0), (2, 0), (4, 3), (8, 2)])
+def test_output_projection_row_slice(M, m, r):
+    """W^O [hidden][Hq d]: rank r multiplies its slice of the attention output by the matching
+    column range of the stored weight (partial sum).  x is itself a column slice of a wider
+    tensor (row stride larger than its width).  K per rank from 4096 (pipelined loop, several
+    slabs per wavefront) down to 512 (one slab each)."""
+    hidden, kin = 256, 4096
+    a_full, w = bits((M, kin), 30 + M), bits((hidden, kin), 31)
+    ov = ow.weight_view(1, r, m, hidden, kin)
+    gv = kv.kv_weight_view_make(1, r, m, hidden, kin)
+    assert (gv.col_start, gv.col_count) == (ov.col_start, ov.col_count)
+    x_slice = dev(a_full)[:, ov.col_start:ov.col_start + ov.col_count]
+    y = kv.kv_linear_view(x_slice, dev(w), gv)
+    torch.cuda.synchronize()
+    want = ow.linear_view(np.ascontiguousarray(a_full[:, ov.col_start:ov.col_start + ov.col_count]), w, ov)
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), want, ov.col_count, f"wo M={M} {r}/{m}")
+
+
+def test_output_rows_outside_the_batch_are_untouched():
+    hidden, kin, M = 64, 256, 5
+    x, w = bits((M, kin), 40), bits((hidden, kin), 41)
+    out = torch.full((8, hidden + 4), 7.0, dtype=torch.bfloat16, device=DEV)
+    kv.kv_linear_view(dev(x), dev(w), kv.kv_weight_view_make(0, 0, 1, hidden, kin), out=out[:M, :hidden])
+    torch.cuda.synchronize()
+    assert (out[M:] == 7.0).all() and (out[:, hidden:] == 7.0).all()
+    check(out[:M, :hidden].contiguous().cpu().view(torch.int16).numpy().view(np.uint16),
+          ow.linear_view(x, w, ow.weight_view(0, 0, 1, hidden, kin)), kin, "padded out")
+
+
+def test_host_checks():
+    L = kv.lib()
+    fake = C.c_void_p(256)
+    v = kv.kv_weight_view_make(0, 1, 2, 256, 512)
+    assert (v.row_start[0], v.row_count[0], v.col_start, v.col_count) == (128, 128, 0, 512)
+    out = kv.kv_weight_view()
+    assert L.kv_weight_view_make(0, 2, 2, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_weight_view_make(1, 0, 3, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_weight_view_make(2, 0, 1, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, None, fake, 128, 4, None) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(fake, 512, fake, 200, 512, C.byref(v), fake, 128, 4, None) == kv.KV_ERR_INVALID_ARG  # view outside the weight
+    assert L.kv_linear_view(fake, 256, fake, 256, 512, C.byref(v), fake, 128, 4, None) == kv.KV_ERR_INVALID_ARG  # ldx < cols
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(v), fake, 64, 4, None) == kv.KV_ERR_INVALID_ARG   # ldy < rows
+    assert L.kv_linear_view(None, 512, fake, 256, 512, C.byref(v), fake, 128, 4, None) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(None, 512, None, 256, 512, C.byref(v), None, 128, 0, None) == kv.KV_OK
+    odd = kv.kv_weight_view_make(1, 0, 8, 256, 512)      # 64 columns: not a whole 128-wide slab
+    assert L.kv_linear_view(fake, 64, fake, 256, 512, C.byref(odd), fake, 256, 4, None) == kv.KV_ERR_UNSUPPORTED
+    thin = kv.kv_weight_view_make(0, 0, 16, 256, 512)    # 16 rows: not a whole 32-row tile
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(thin), fake, 16, 4, None) == kv.KV_ERR_UNSUPPORTED
