@@ -210,16 +210,21 @@ int kv_weight_view_fused_qkv(const kv_geometry* g, int64_t hidden, int r, int m,
  *   x       device, bf16 [M][view->col_count], row stride ldx elements          (read)
  *   w_full  device, bf16 [w_rows][ldw]: the whole stored weight, ldw its row length (read)
  *   y       device, bf16 [M][sum of row_count], row stride ldy elements          (written)
+ *   workspace device scratch of at least kv_linear_view_workspace_bytes(view, M) bytes (may be
+ *           0: then null is accepted), 16-byte aligned; contents need not be initialised
  * fp32 accumulation, one rounding to bf16 at the end.  For the row-parallel layer y is the
  * rank's partial sum (the all-reduce over ranks is the caller's).  Tuned for decode batches (M up
  * to a few hundred); any M is accepted.
  * Errors: KV_ERR_INVALID_ARG (null pointers, view outside the weight, strides too small),
+ * KV_ERR_WORKSPACE,
  * KV_ERR_UNSUPPORTED (col_count not a multiple of 128, a row segment not a multiple of 32,
  * col_start / ldx / ldw not multiples of 8 elements, ldy not a multiple of 4, pointers not
  * 16-byte aligned), KV_ERR_HIP.
  */
+size_t kv_linear_view_workspace_bytes(const kv_weight_view* view, int M);
 int kv_linear_view(const void* x, int64_t ldx, const void* w_full, int64_t w_rows, int64_t ldw,
-                   const kv_weight_view* view, void* y, int64_t ldy, int M, void* hip_stream);
+                   const kv_weight_view* view, void* y, int64_t ldy, int M, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
 
 /*
  * kv_repack -- move KV rows between two arrangements inside one pool, bit-exactly.  This

@@ -63,7 +63,9 @@ def lib() -> C.CDLL:
                                      C.c_float, vp]
     L.kv_weight_view_make.argtypes = [C.c_int, C.c_int, C.c_int, i64, i64, vp]
     L.kv_weight_view_fused_qkv.argtypes = [vp, i64, C.c_int, C.c_int, vp]
-    L.kv_linear_view.argtypes = [vp, i64, vp, i64, i64, vp, vp, i64, C.c_int, vp]
+    L.kv_linear_view.argtypes = [vp, i64, vp, i64, i64, vp, vp, i64, C.c_int, vp, C.c_size_t, vp]
+    L.kv_linear_view_workspace_bytes.argtypes = [vp, C.c_int]
+    L.kv_linear_view_workspace_bytes.restype = C.c_size_t
     L.kv_repack.argtypes = [vp, i64, vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp]
     L.kv_append.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp, C.c_int, vp]
     L.kv_validate_tables.argtypes = [vp, i64, vp, i64, vp, C.c_int, vp, vp, i64, vp]
@@ -283,16 +285,22 @@ def kv_weight_view_fused_qkv(n_q_heads: int, n_kv_heads: int, head_dim: int, hid
 
 
 def kv_linear_view(x: torch.Tensor, w_full: torch.Tensor, view: kv_weight_view,
-                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                   stream=None) -> torch.Tensor:
     """y[M][view rows] (bf16) = x @ W_active^T, W_active = ``view`` of the stored ``w_full`` [out][in]."""
     if x.dim() != 2 or w_full.dim() != 2 or x.shape[1] != view.col_count:
         raise ValueError("x must be [M][view.col_count], w_full [out][in]")
     M = int(x.shape[0])
     if out is None:
         out = torch.empty((M, view.n_rows), dtype=torch.bfloat16, device=x.device)
+    need = int(lib().kv_linear_view_workspace_bytes(C.byref(view), M))
+    if workspace is None:
+        workspace = _workspace(x.device, need)
     rc = lib().kv_linear_view(_dev_rows(x, _BF16, "x"), x.stride(0), _dev_rows(w_full, _BF16, "w_full"),
                               int(w_full.shape[0]), w_full.stride(0), C.byref(view),
-                              _dev_rows(out, _BF16, "out"), out.stride(0), M, _stream_ptr(stream))
+                              _dev_rows(out, _BF16, "out"), out.stride(0), M,
+                              _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(),
+                              _stream_ptr(stream))
     _check(rc, "kv_linear_view")
     return out
 

@@ -12,8 +12,11 @@
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
 // with 16x16x32 bf16 MFMA (A operand = 16 weight rows, B operand = 16 batch rows; both are read
 // in operand order straight from global memory, 16 bytes per lane), the next slab's operands in
-// flight while the current one is consumed.  The four partial tiles are summed through LDS and
-// stored as bf16.
+// flight while the current one is consumed.  The four partial tiles are summed through LDS.
+// A decode batch gives few such workgroups for 256 compute units, and a wavefront streams at the
+// pace memory latency allows, so the input dimension is also cut over `splits` workgroups
+// (grid.z): each then leaves an fp32 partial tile in the workspace and a second, small kernel adds
+// the splits in a fixed order and rounds to bf16 (deterministic; no atomics).
 #include <string.h>
 
 #include "decode_common.h"
@@ -39,6 +42,8 @@ struct linear_args {
     int32_t n_seg;
     int64_t seg_start[3];   // first stored row of each segment
     int32_t seg_first[4];   // first logical row of each segment; seg_first[n_seg] = Nl
+    int32_t splits;         // workgroups sharing the input dimension of one output tile
+    float* part;            // [splits][M][Nl] fp32 when splits > 1
 };
 
 struct slab_regs {
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
         for (int rb = 0; rb < kRowBlocks; ++rb)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                t.a[rb][kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase[rb] + off + kk * 64));
+                t.a[rb][kk] = *reinterpret_cast<const kv_u32x4*>(wbase[rb] + off + kk * 64);
 #pragma unroll
         for (int cb = 0; cb < kColBlocks; ++cb)
 #pragma unroll
@@ -102,8 +107,11 @@ __global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
                                                                          acc[rb][cb], 0, 0, 0);
     };
 
-    const int n_slabs = p.Kl / kSlab;
-    int slab = wave;
+    // this workgroup's slabs: [first, n_slabs)
+    const int total_slabs = p.Kl / kSlab;
+    const int per_split = (total_slabs + p.splits - 1) / p.splits;
+    const int n_slabs = min(total_slabs, ((int)blockIdx.z + 1) * per_split);
+    int slab = (int)blockIdx.z * per_split + wave;
     if (slab + 12 < n_slabs) {
         // steady state without conditional loads: two slabs in flight
         slab_regs ta, tb;
@@ -148,7 +156,10 @@ __global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
         const int ln = rec & 63, blk = rec >> 6;
         const int cb = blk % kColBlocks, rb = blk / kColBlocks;
         const int m = m0 + 16 * cb + (ln & 15);
-        if (m < p.M) {
+        if (m < p.M && p.splits > 1) {
+            float* dst = p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + n0 + 16 * rb + 4 * (ln >> 4);
+            *reinterpret_cast<f32x4*>(dst) = s;
+        } else if (m < p.M) {
             uint16_t* dst = p.y + (int64_t)m * p.ldy + n0 + 16 * rb + 4 * (ln >> 4);
             uint2 pk;
             pk.x = pack_bf16x2(s[0], s[1]);
@@ -158,7 +169,51 @@ __global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
     }
 }
 
+// y[m][n .. n + 4) = bf16(sum over splits of part[z][m][n .. n + 4)), splits added in order
+__global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
+{
+    const int64_t quads = (int64_t)p.M * (p.Nl / 4);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= quads) return;
+    const int64_t m = i / (p.Nl / 4), n = (i - m * (p.Nl / 4)) * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < p.splits; ++z)
+        s += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)z * p.M + m) * p.Nl + n);
+    uint2 pk;
+    pk.x = pack_bf16x2(s[0], s[1]);
+    pk.y = pack_bf16x2(s[2], s[3]);
+    *reinterpret_cast<uint2*>(p.y + m * p.ldy + n) = pk;
+}
+
+// Workgroups sharing the input dimension of one output tile: enough for about three workgroups
+// per compute unit in total, at least one slab per wavefront, at most 16.
+int pick_splits(int64_t tiles, int total_slabs)
+{
+    int s = (int)((768 + tiles - 1) / tiles);
+    s = s < 1 ? 1 : s;
+    s = s > 16 ? 16 : s;
+    const int most = total_slabs / 4 > 0 ? total_slabs / 4 : 1;
+    return s > most ? most : s;
+}
+
+int64_t view_rows(const kv_weight_view* view)
+{
+    int64_t n = 0;
+    for (int i = 0; i < view->n_segments && i < 3; ++i) n += view->row_count[i];
+    return n;
+}
+
 }  // namespace
+
+extern "C" size_t kv_linear_view_workspace_bytes(const kv_weight_view* view, int M)
+{
+    if (!view || M <= 0 || view->n_segments < 1 || view->n_segments > 3 || view->col_count <= 0) return 0;
+    const int64_t n_l = view_rows(view);
+    if (n_l <= 0) return 0;
+    const int64_t tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks) * (n_l / (16 * kRowBlocks));
+    const int splits = pick_splits(tiles > 0 ? tiles : 1, (int)(view->col_count / kSlab));
+    return splits > 1 ? (size_t)splits * M * n_l * 4 : 0;
+}
 
 extern "C" int kv_weight_view_make(int dim, int r, int m, int64_t n_rows, int64_t n_cols, kv_weight_view* out)
 {
@@ -201,7 +256,8 @@ extern "C" int kv_weight_view_fused_qkv(const kv_geometry* g, int64_t hidden, in
 }
 
 extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, int64_t w_rows, int64_t ldw,
-                              const kv_weight_view* view, void* y, int64_t ldy, int M, void* hip_stream)
+                              const kv_weight_view* view, void* y, int64_t ldy, int M, void* workspace,
+                              size_t workspace_bytes, void* hip_stream)
 {
     if (!view || M < 0 || view->n_segments < 1 || view->n_segments > 3 || w_rows <= 0 || ldw <= 0)
         return KV_ERR_INVALID_ARG;
@@ -246,9 +302,20 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
     const int64_t n_tiles = n_l / (16 * kRowBlocks);
     if (m_tiles > 0x7fffffff || n_tiles > 65535) return KV_ERR_UNSUPPORTED;
+    p.splits = pick_splits(m_tiles * n_tiles, p.Kl / kSlab);
+    p.part = (float*)workspace;
+    if (p.splits > 1) {
+        if (!workspace || ((uintptr_t)workspace & 15)) return KV_ERR_INVALID_ARG;
+        if (workspace_bytes < (size_t)p.splits * M * n_l * 4) return KV_ERR_WORKSPACE;
+    }
     hipStream_t st = (hipStream_t)hip_stream;
     const int slot = kv_prof_begin(KV_PROF_LINEAR, st);
-    hipLaunchKernelGGL(linear_view_kernel, dim3((unsigned)m_tiles, (unsigned)n_tiles), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL(linear_view_kernel, dim3((unsigned)m_tiles, (unsigned)n_tiles, (unsigned)p.splits),
+                       dim3(kThreads), 0, st, p);
+    if (p.splits > 1) {
+        const int64_t quads = (int64_t)M * (n_l / 4);
+        hipLaunchKernelGGL(linear_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p);
+    }
     kv_prof_end(KV_PROF_LINEAR, slot, st);
     return kv_record_hip_error(hipGetLastError(), "kv_linear_view launch");
 }
