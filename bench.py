@@ -85,7 +85,12 @@ def main():
         n_cu = torch.cuda.get_device_properties(0).multi_processor_count
         rd = harness.time_calls(lambda i: kv.kv_probe_read(src, n_cu), iters, 3)
         cp = harness.time_calls(lambda i: kv.kv_probe_copy(dst, src, n_cu), iters, 3)
+        # the paged pattern: a random 5/6 of the 64 KiB blocks of the buffer, each read whole
+        n_blk = n_bytes // 65536
+        ids = torch.randperm(n_blk, device="cuda", dtype=torch.int32)[: n_blk * 5 // 6].contiguous()
+        pg = harness.time_calls(lambda i: kv.kv_probe_read_blocks(src, ids, 65536, n_cu), iters, 3)
         return {"read_GBps": round(n_bytes / rd / 1e6, 1), "copy_read_plus_write_GBps": round(2 * n_bytes / cp / 1e6, 1),
+                "paged_64KiB_blocks_read_GBps": round(int(ids.numel()) * 65536 / pg / 1e6, 1),
                 "bytes": n_bytes, "workgroups": n_cu}
 
     if args.probe:
@@ -200,6 +205,71 @@ def main():
                 del oc, orun
                 torch.cuda.empty_cache()
         extras["other_workloads"] = others
+
+        # --- rows beyond the headline path, each against its own roofline -------------------------
+        MFMA_BF16_PEAK_TFLOPS = 2500.0
+        mw = wl.WORKLOADS["llama8b_tp_b128"]
+        mc = harness.build_mixed_case(mw, 2, 0)
+        ms = harness.time_calls(mc.run, max(10, args.steps // 2), 5)
+        extras["mixed_layout_decode"] = {
+            "workload": mw.name, "what": "TP2 rank 0; every other sequence read in place from DP-layout blocks; one launch",
+            "us_per_layer": round(ms * 1e3, 2), "GBps": round(mc.kv_bytes / (ms * 1e-3) / 1e9, 1),
+            "pct_hbm_peak": round(100 * mc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+        del mc
+        torch.cuda.empty_cache()
+
+        pre = []
+        w8 = wl.Workload("llama8b_recompute", 90, 32, 8, 128, 16, 8, "fixed", ())
+        for label, tr, ctx, ql in (("8 prompts of 4096 tokens, whole", (0, 1, 0), [4096] * 8, [4096] * 8),
+                                   ("8 prompts of 4096 tokens, whole", (1, 2, 0), [4096] * 8, [4096] * 8),
+                                   ("16 chunks of 512 tokens on 8192 cached", (0, 1, 0), [8192] * 16, [512] * 16)):
+            pc = harness.build_prefill_case(w8, tr, ctx, ql)
+            kv.kv_profile_enable(True)
+            ms = harness.time_calls(pc.run, 10, 2)
+            k_ms, k_n = kv.kv_profile_read(kv.KV_PROF_PREFILL)
+            kv.kv_profile_enable(False)
+            k_ms /= max(k_n, 1)
+            pre.append({"what": label, "view": list(tr), "ms": round(ms, 4), "kernel_ms": round(k_ms, 4),
+                        "algorithmic_TFLOP": round(pc.flops / 1e12, 3),
+                        "roofline": {"bound": "mfma", "achieved": round(pc.flops / k_ms / 1e9, 1),
+                                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": round(pc.flops / k_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}})
+            del pc
+            torch.cuda.empty_cache()
+        extras["paged_prefill_attn"] = pre
+
+        lin = []
+        hq, hkv, d, hidden = 32, 8, 128, 4096
+        g = torch.Generator(device="cuda")
+        g.manual_seed(wl.SEED_BASE + 777)
+        n_w = 6   # distinct weights cycled through, so that no call finds its weight in the last-level cache
+        wqkv = [torch.randn(((hq + 2 * hkv) * d, hidden), generator=g, device="cuda").to(torch.bfloat16) for _ in range(n_w)]
+        wo = [torch.randn((hidden, hq * d), generator=g, device="cuda").to(torch.bfloat16) for _ in range(n_w)]
+        for M, m in ((64, 1), (64, 2), (128, 2), (256, 8)):
+            x = torch.randn((M, hidden), generator=g, device="cuda").to(torch.bfloat16)
+            a_full = torch.randn((M, hq * d), generator=g, device="cuda").to(torch.bfloat16)
+            for name, view, xin, ws in (("qkv", kv.kv_weight_view_fused_qkv(hq, hkv, d, hidden, 0, m), x, wqkv),
+                                        ("wo", kv.kv_weight_view_make(1, 0, m, hidden, hq * d), None, wo)):
+                if xin is None:
+                    xin = a_full[:, :view.col_count]
+                out = torch.empty((M, view.n_rows), dtype=torch.bfloat16, device="cuda")
+                for i in range(4):
+                    kv.kv_linear_view(xin, ws[i % n_w], view, out=out)
+                torch.cuda.synchronize()
+                kv.kv_profile_enable(True)
+                for i in range(24):
+                    kv.kv_linear_view(xin, ws[i % n_w], view, out=out)
+                torch.cuda.synchronize()
+                k_ms, k_n = kv.kv_profile_read(kv.KV_PROF_LINEAR)
+                kv.kv_profile_enable(False)
+                k_ms /= max(k_n, 1)
+                wbytes = view.n_rows * view.col_count * 2
+                lin.append({"layer": name, "M": M, "tp_degree": m, "weight_slice_bytes": wbytes,
+                            "kernel_us": round(k_ms * 1e3, 2),
+                            "roofline": {"bound": "hbm", "achieved": round(wbytes / k_ms / 1e6, 1), "peak": HBM_PEAK_GBPS,
+                                         "unit": "GB/s", "frac": round(wbytes / k_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+                            "TFLOPs": round(2.0 * M * view.n_rows * view.col_count / k_ms / 1e9, 1)})
+        extras["kv_linear_view"] = lin
         result["extras"] = extras
 
     print(json.dumps(result))

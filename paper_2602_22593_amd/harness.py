@@ -104,6 +104,51 @@ def build_decode_case(w: wl.Workload, triple, device="cuda:0", n_copies: int = 1
 
 
 @dataclass
+class MixedCase:
+    views: list
+    ctx: np.ndarray
+    q: torch.Tensor
+    out: torch.Tensor
+    pool: torch.Tensor
+    table_dev: torch.Tensor
+    ctx_dev: torch.Tensor
+    ids_dev: torch.Tensor
+    workspace: torch.Tensor
+    kv_bytes: int
+
+    def run(self, i: int = 0) -> None:
+        kv.paged_decode_attn_mixed(self.q, self.pool, self.table_dev, self.ctx_dev, self.ids_dev, self.views,
+                                   int(self.ctx.max()), out=self.out, workspace=self.workspace)
+
+
+def build_mixed_case(w: wl.Workload, p: int, r: int, device="cuda:0", slack: float = 1.2) -> MixedCase:
+    """The workload's batch with every other sequence stored in DP-layout blocks (read through rank
+    r's alias view) and the rest in the TP layout of degree p: one pool, one table."""
+    views = [make_view(w, (kv.KV_LAYOUT_TP, p, r)), make_view(w, (kv.KV_LAYOUT_DP, p, r))]
+    ctx = wl.draw_ctx_lens(w)
+    ids = (np.arange(len(ctx)) % 2).astype(np.int32)
+    caps = np.where(ids == 0, views[0].block_tokens, views[1].block_tokens).astype(np.int64)
+    need = (ctx.astype(np.int64) + caps - 1) // caps
+    perm = wl.shuffled_pool(int(need.sum()), slack, wl.generator(w.index, wl.SUB_PERM + 500))
+    cols = max(int(need.max()), (int(ctx.max()) + int(caps.min()) - 1) // int(caps.min()))
+    table = np.full((len(ctx), cols), -1, dtype=np.int32)
+    used = 0
+    for s, k in enumerate(need):
+        table[s, :k] = perm[used:used + int(k)]
+        used += int(k)
+    pool = random_pool(len(perm), views[0].block_bytes // 2, wl.SEED_BASE + 10 * w.index + wl.SUB_DATA + 5000, device)
+    q_full = wl.queries(w)
+    lo = r * views[0].n_q_local
+    q = torch.from_numpy(np.ascontiguousarray(q_full[:, lo:lo + views[0].n_q_local]).view(np.int16)) \
+        .to(device).view(torch.bfloat16)
+    ws = torch.empty(max(kv.paged_decode_attn_workspace_bytes(views[0], len(ctx), int(ctx.max())), 256),
+                     dtype=torch.uint8, device=device)
+    kv_bytes = int(ctx.astype(np.int64).sum()) * views[0].n_kv_local * views[0].head_dim * 2 * 2
+    return MixedCase(views, ctx, q, torch.empty_like(q), pool, torch.from_numpy(table).to(device),
+                     torch.from_numpy(ctx).to(device), torch.from_numpy(ids).to(device), ws, kv_bytes)
+
+
+@dataclass
 class PrefillCase:
     view: kv.KVView
     ctx: np.ndarray
