@@ -217,7 +217,7 @@ int kv_weight_view_fused_qkv(const kv_geometry* g, int64_t hidden, int r, int m,
  * to a few hundred); any M is accepted.
  * Errors: KV_ERR_INVALID_ARG (null pointers, view outside the weight, strides too small),
  * KV_ERR_WORKSPACE,
- * KV_ERR_UNSUPPORTED (col_count not a multiple of 128, a row segment not a multiple of 32,
+ * KV_ERR_UNSUPPORTED (col_count not a multiple of 128, a row segment not a multiple of 64,
  * col_start / ldx / ldw not multiples of 8 elements, ldy not a multiple of 4, pointers not
  * 16-byte aligned), KV_ERR_HIP.
  */

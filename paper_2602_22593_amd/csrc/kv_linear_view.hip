@@ -6,17 +6,19 @@
 // copied: the kernel addresses the full matrix with its own leading dimension.
 //
 // Shaped for decode batches (M up to a few hundred rows): the weight slice is streamed from HBM
-// once per 64 batch rows and is the dominant traffic; x is small and comes from the caches.
-// A workgroup owns 32 logical weight rows x 64 batch rows; its four wavefronts split the input
-// dimension in slabs of 128 (wavefront w takes slabs w, w + 4, ...), each accumulating
+// once per 64 batch rows and is the dominant traffic; x is small, but every weight row needs all
+// of it, so it must be shared: a workgroup of four wavefronts owns 64 logical weight rows (16 per
+// wavefront) x 64 batch rows and walks its part of the input dimension in steps of 128.  Per
+// step the workgroup stages the x slab (64 rows x 128) in LDS once, laid out in MFMA operand
+// order so that each B operand is one contiguous kilobyte, and every wavefront accumulates
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
-// with 16x16x32 bf16 MFMA (A operand = 16 weight rows, B operand = 16 batch rows; both are read
-// in operand order straight from global memory, 16 bytes per lane), the next slab's operands in
-// flight while the current one is consumed.  The four partial tiles are summed through LDS.
+// with 16x16x32 bf16 MFMA, taking its A operand (16 weight rows) straight from global memory in
+// operand order.  The next step's W and x pieces are in flight while the current one is
+// consumed; LDS is double buffered, one barrier per step.
 // A decode batch gives few such workgroups for 256 compute units, and a wavefront streams at the
-// pace memory latency allows, so the input dimension is also cut over `splits` workgroups
-// (grid.z): each then leaves an fp32 partial tile in the workspace and a second, small kernel adds
-// the splits in a fixed order and rounds to bf16 (deterministic; no atomics).
+// pace memory latency allows, so the input dimension is cut over `splits` workgroups (grid.z):
+// each then leaves an fp32 partial tile in the workspace and a second, small kernel adds the
+// splits in a fixed order and rounds to bf16 (deterministic; no atomics).
 #include <string.h>
 
 #include "decode_common.h"
@@ -26,7 +28,7 @@ using namespace kvdec;
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowBlocks = 2;   // 16-row blocks of the weight per workgroup
+constexpr int kTileRows = 64;   // logical weight rows per workgroup: 16 per wavefront
 constexpr int kColBlocks = 4;   // 16-row blocks of x per workgroup
 constexpr int kSlab = 128;      // input features per step
 
@@ -46,125 +48,96 @@ struct linear_args {
     float* part;            // [splits][M][Nl] fp32 when splits > 1
 };
 
-struct slab_regs {
-    kv_u32x4 a[kRowBlocks][4];
-    kv_u32x4 b[kColBlocks][4];
-};
-
-__global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
+__global__ __launch_bounds__(kThreads, 4) void linear_view_kernel(linear_args p)
 {
-    __shared__ float s_part[4][kRowBlocks * kColBlocks * 256];
+    // x slab in operand order: piece (kk, cb, quad, c) = x[16 cb + c][32 kk + 8 quad .. + 8) of the
+    // step sits at ((kk * 4 + cb) * 4 + quad) * 16 + (c ^ (4 kk + quad)): a B operand is one
+    // contiguous kilobyte, and the XOR spreads the row-wise staging writes over all banks
+    __shared__ kv_u32x4 s_x[2][4 * kColBlocks * 64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, quad = lane >> 4;
     const int m0 = blockIdx.x * (16 * kColBlocks);
-    const int n0 = blockIdx.y * (16 * kRowBlocks);
+    const int n0 = blockIdx.y * kTileRows;
 
-    // the 32 logical rows of this workgroup lie in one segment (segment sizes are multiples of 32)
+    // the 64 logical rows of this workgroup lie in one segment (segment sizes are multiples of 64)
     int seg = 0;
     while (seg + 1 < p.n_seg && n0 >= p.seg_first[seg + 1]) ++seg;
     const int64_t phys0 = p.seg_start[seg] + (n0 - p.seg_first[seg]);
+    const char* wbase = reinterpret_cast<const char*>(p.w + (phys0 + 16 * wave + r) * p.ldw + p.col_start) + quad * 16;
 
-    const char* wbase[kRowBlocks];
+    // staging: thread t moves pieces t, t + 256, t + 512, t + 768 of the slab; piece id = 16 row + q,
+    // q = 4 kk + quad the 16-byte piece within the row's 128 elements (rows past M repeat the last)
+    const char* xsrc[4];
+    int xdst[4];
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb)
-        wbase[rb] = reinterpret_cast<const char*>(p.w + (phys0 + 16 * rb + r) * p.ldw + p.col_start) + quad * 16;
-    const char* xbase[kColBlocks];
-#pragma unroll
-    for (int cb = 0; cb < kColBlocks; ++cb) {
-        const int row = min(m0 + 16 * cb + r, p.M - 1);  // rows past M repeat the last one; not stored
-        xbase[cb] = reinterpret_cast<const char*>(p.x + (int64_t)row * p.ldx) + quad * 16;
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
+        xsrc[i] = reinterpret_cast<const char*>(p.x + (int64_t)min(m0 + row, p.M - 1) * p.ldx) + q * 16;
+        xdst[i] = (((q >> 2) * kColBlocks + (row >> 4)) * 4 + (q & 3)) * 16 + ((row & 15) ^ q);
     }
 
-    auto fetch = [&](slab_regs& t, int slab) {
-        const int64_t off = (int64_t)slab * (kSlab * 2);
+    // this workgroup's steps: [step, last)
+    const int total = p.Kl / kSlab;
+    const int per_split = (total + p.splits - 1) / p.splits;
+    int step = (int)blockIdx.z * per_split;
+    const int last = min(total, step + per_split);
+
+    f32x4 acc[kColBlocks];
 #pragma unroll
-        for (int rb = 0; rb < kRowBlocks; ++rb)
+    for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    kv_u32x4 a_cur[4], a_nxt[4], x_nxt[4];
+    auto fetch = [&](kv_u32x4 (&a)[4], int st) {
+        const int64_t off = (int64_t)st * (kSlab * 2);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                t.a[rb][kk] = *reinterpret_cast<const kv_u32x4*>(wbase[rb] + off + kk * 64);
+        for (int kk = 0; kk < 4; ++kk)
+            a[kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase + off + kk * 64));
 #pragma unroll
-        for (int cb = 0; cb < kColBlocks; ++cb)
+        for (int i = 0; i < 4; ++i) x_nxt[i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off);
+    };
+    auto stash = [&](int buf) {
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                t.b[cb][kk] = *reinterpret_cast<const kv_u32x4*>(xbase[cb] + off + kk * 64);
+        for (int i = 0; i < 4; ++i) s_x[buf][xdst[i]] = x_nxt[i];
     };
 
-    f32x4 acc[kRowBlocks][kColBlocks];
-#pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < kColBlocks; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    auto consume = [&](const slab_regs& t) {
+    if (step < last) {
+        fetch(a_cur, step);
+        stash(0);
+    }
+    __syncthreads();
+    for (int buf = 0; step < last; ++step, buf ^= 1) {
+        const bool more = step + 1 < last;
+        if (more) fetch(a_nxt, step + 1);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-            for (int rb = 0; rb < kRowBlocks; ++rb)
+            for (int cb = 0; cb < kColBlocks; ++cb) {
+                const kv_u32x4 b = s_x[buf][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_cur[kk]), as_bf16x8(b), acc[cb], 0, 0, 0);
+            }
+        if (more) {
+            stash(buf ^ 1);
 #pragma unroll
-                for (int cb = 0; cb < kColBlocks; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.a[rb][kk]), as_bf16x8(t.b[cb][kk]),
-                                                                         acc[rb][cb], 0, 0, 0);
-    };
-
-    // this workgroup's slabs: [first, n_slabs)
-    const int total_slabs = p.Kl / kSlab;
-    const int per_split = (total_slabs + p.splits - 1) / p.splits;
-    const int n_slabs = min(total_slabs, ((int)blockIdx.z + 1) * per_split);
-    int slab = (int)blockIdx.z * per_split + wave;
-    if (slab + 12 < n_slabs) {
-        // steady state without conditional loads: two slabs in flight
-        slab_regs ta, tb;
-        fetch(ta, slab);
-        fetch(tb, slab + 4);
-        do {
-            consume(ta);
-            fetch(ta, slab + 8);
-            consume(tb);
-            fetch(tb, slab + 12);
-            slab += 8;
-        } while (slab + 12 < n_slabs);
-        // slabs `slab` and `slab + 4` are loaded; `slab + 8` may remain
-        consume(ta);
-        if (slab + 8 < n_slabs) fetch(ta, slab + 8);
-        consume(tb);
-        if (slab + 8 < n_slabs) consume(ta);
-    } else {
-        slab_regs ta;
-        for (; slab < n_slabs; slab += 4) {
-            fetch(ta, slab);
-            consume(ta);
+            for (int kk = 0; kk < 4; ++kk) a_cur[kk] = a_nxt[kk];
         }
+        __syncthreads();
     }
 
-    // ---- sum the four wavefronts' tiles, convert, store ------------------------------------------
-    // acc[rb][cb][i] = y[m0 + 16 cb + r][n0 + 16 rb + 4 quad + i]
+    // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 wave + 4 quad + i]
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < kColBlocks; ++cb)
-            *reinterpret_cast<f32x4*>(&s_part[wave][((rb * kColBlocks + cb) * 64 + lane) * 4]) = acc[rb][cb];
-    __syncthreads();
-    // lane layout of the tile: thread t handles two (rb, cb, lane) records
-#pragma unroll
-    for (int k = 0; k < (kRowBlocks * kColBlocks * 64) / kThreads; ++k) {
-        const int rec = tid + k * kThreads;
-        const f32x4 s = *reinterpret_cast<const f32x4*>(&s_part[0][rec * 4]) +
-                        *reinterpret_cast<const f32x4*>(&s_part[1][rec * 4]) +
-                        *reinterpret_cast<const f32x4*>(&s_part[2][rec * 4]) +
-                        *reinterpret_cast<const f32x4*>(&s_part[3][rec * 4]);
-        const int ln = rec & 63, blk = rec >> 6;
-        const int cb = blk % kColBlocks, rb = blk / kColBlocks;
-        const int m = m0 + 16 * cb + (ln & 15);
-        if (m < p.M && p.splits > 1) {
-            float* dst = p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + n0 + 16 * rb + 4 * (ln >> 4);
-            *reinterpret_cast<f32x4*>(dst) = s;
-        } else if (m < p.M) {
-            uint16_t* dst = p.y + (int64_t)m * p.ldy + n0 + 16 * rb + 4 * (ln >> 4);
+    for (int cb = 0; cb < kColBlocks; ++cb) {
+        const int m = m0 + 16 * cb + r;
+        if (m >= p.M) continue;
+        const int n = n0 + 16 * wave + 4 * quad;
+        if (p.splits > 1) {
+            *reinterpret_cast<f32x4*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + n) = acc[cb];
+        } else {
             uint2 pk;
-            pk.x = pack_bf16x2(s[0], s[1]);
-            pk.y = pack_bf16x2(s[2], s[3]);
-            *reinterpret_cast<uint2*>(dst) = pk;
+            pk.x = pack_bf16x2(acc[cb][0], acc[cb][1]);
+            pk.y = pack_bf16x2(acc[cb][2], acc[cb][3]);
+            *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + n) = pk;
         }
     }
 }
@@ -185,14 +158,15 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
     *reinterpret_cast<uint2*>(p.y + m * p.ldy + n) = pk;
 }
 
-// Workgroups sharing the input dimension of one output tile: enough for about three workgroups
-// per compute unit in total, at least one slab per wavefront, at most 16.
-int pick_splits(int64_t tiles, int total_slabs)
+// Workgroups sharing the input dimension of one output tile: enough for about two workgroups
+// per compute unit in total (measured best for the Llama-8B projections: more splits only add
+// partial traffic), at least two steps each, at most 16.
+int pick_splits(int64_t tiles, int total_steps)
 {
-    int s = (int)((768 + tiles - 1) / tiles);
+    int s = (int)((512 + tiles - 1) / tiles);
     s = s < 1 ? 1 : s;
     s = s > 16 ? 16 : s;
-    const int most = total_slabs / 4 > 0 ? total_slabs / 4 : 1;
+    const int most = total_steps / 2 > 0 ? total_steps / 2 : 1;
     return s > most ? most : s;
 }
 
@@ -210,7 +184,7 @@ extern "C" size_t kv_linear_view_workspace_bytes(const kv_weight_view* view, int
     if (!view || M <= 0 || view->n_segments < 1 || view->n_segments > 3 || view->col_count <= 0) return 0;
     const int64_t n_l = view_rows(view);
     if (n_l <= 0) return 0;
-    const int64_t tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks) * (n_l / (16 * kRowBlocks));
+    const int64_t tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks) * (n_l / kTileRows);
     const int splits = pick_splits(tiles > 0 ? tiles : 1, (int)(view->col_count / kSlab));
     return splits > 1 ? (size_t)splits * M * n_l * 4 : 0;
 }
@@ -272,13 +246,13 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
         return KV_ERR_INVALID_ARG;
     if (M == 0) return KV_OK;
     if (!x || !w_full || !y) return KV_ERR_INVALID_ARG;
-    // 16-byte operand loads, whole 128-wide slabs, 32-row workgroup tiles inside one segment
+    // 16-byte operand loads, whole 128-wide steps, 64-row workgroup tiles inside one segment
     if (view->col_count % kSlab != 0 || view->col_start % 8 != 0 || ldx % 8 != 0 || ldw % 8 != 0 || ldy % 4 != 0 ||
         ((uintptr_t)x & 15) || ((uintptr_t)w_full & 15) || ((uintptr_t)y & 7) || n_l > 0x7fffffff ||
         view->col_count > 0x7fffffff)
         return KV_ERR_UNSUPPORTED;
     for (int i = 0; i < view->n_segments; ++i)
-        if (view->row_count[i] % (16 * kRowBlocks) != 0) return KV_ERR_UNSUPPORTED;
+        if (view->row_count[i] % kTileRows != 0) return KV_ERR_UNSUPPORTED;
     linear_args p;
     p.x = (const uint16_t*)x;
     p.ldx = ldx;
@@ -300,7 +274,7 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     p.seg_first[3] = first;
     for (int i = view->n_segments; i < 4; ++i) p.seg_first[i] = first;
     const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
-    const int64_t n_tiles = n_l / (16 * kRowBlocks);
+    const int64_t n_tiles = n_l / kTileRows;
     if (m_tiles > 0x7fffffff || n_tiles > 65535) return KV_ERR_UNSUPPORTED;
     p.splits = pick_splits(m_tiles * n_tiles, p.Kl / kSlab);
     p.part = (float*)workspace;
@@ -319,3 +293,4 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     kv_prof_end(KV_PROF_LINEAR, slot, st);
     return kv_record_hip_error(hipGetLastError(), "kv_linear_view launch");
 }
+

@@ -111,5 +111,5 @@ def test_host_checks():
     assert need > 0 and need % (8 * 256 * 4) == 0
     assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, fake, need - 1, None) == kv.KV_ERR_WORKSPACE
     assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, None, need, None) == kv.KV_ERR_INVALID_ARG
-    thin = kv.kv_weight_view_make(0, 0, 16, 256, 512)    # 16 rows: not a whole 32-row tile
-    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(thin), fake, 16, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED
+    thin = kv.kv_weight_view_make(0, 0, 8, 256, 512)     # 32 rows: not a whole 64-row tile
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(thin), fake, 32, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED
