@@ -170,6 +170,51 @@ def test_mixed_entry_point_checks_without_a_gpu():
     assert call([a64, b64]) == kv.KV_ERR_UNSUPPORTED
 
 
+def test_weight_view_and_linear_view_checks_without_a_gpu():
+    L = kv.lib()
+    fake = C.c_void_p(256)
+    v = kv.kv_weight_view_make(0, 1, 2, 256, 512)
+    assert (v.row_start[0], v.row_count[0], v.col_start, v.col_count) == (128, 128, 0, 512)
+    out = kv.kv_weight_view()
+    assert L.kv_weight_view_make(0, 2, 2, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_weight_view_make(1, 0, 3, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_weight_view_make(2, 0, 1, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, None, fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(fake, 512, fake, 200, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG  # view outside the weight
+    assert L.kv_linear_view(fake, 256, fake, 256, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG  # ldx < cols
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(v), fake, 64, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG   # ldy < rows
+    assert L.kv_linear_view(None, 512, fake, 256, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG
+    assert L.kv_linear_view(None, 512, None, 256, 512, C.byref(v), None, 128, 0, None, 0, None) == kv.KV_OK
+    odd = kv.kv_weight_view_make(1, 0, 8, 256, 512)      # 64 columns: not a whole 128-wide slab
+    assert L.kv_linear_view(fake, 64, fake, 256, 512, C.byref(odd), fake, 256, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED
+    big = kv.kv_weight_view_make(0, 0, 1, 256, 4096)     # few tiles, many slabs: the input dimension is split
+    need = L.kv_linear_view_workspace_bytes(C.byref(big), 8)
+    assert need > 0 and need % (8 * 256 * 4) == 0
+    assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, fake, need - 1, None) == kv.KV_ERR_WORKSPACE
+    assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, None, need, None) == kv.KV_ERR_INVALID_ARG
+    thin = kv.kv_weight_view_make(0, 0, 8, 256, 512)     # 32 rows: not a whole 64-row tile
+    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(thin), fake, 32, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED
+
+
+def test_prefill_entry_point_checks_without_a_gpu():
+    L = kv.lib()
+    fake = C.c_void_p(256)
+    v = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_DP, 1, 0)          # head_dim 64
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+        == kv.KV_ERR_UNSUPPORTED
+    v = kv.kv_view_create(48, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)        # group of 6
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+        == kv.KV_ERR_UNSUPPORTED
+    v = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 65, v.handle, 0.0, None) \
+        == kv.KV_ERR_INVALID_ARG                                         # max_q_len > max_ctx_len
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 3, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+        == kv.KV_ERR_INVALID_ARG                                         # table too narrow
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, None, 1, 64, 8, v.handle, 0.0, None) \
+        == kv.KV_ERR_INVALID_ARG
+    assert L.paged_prefill_attn(None, None, None, 0, None, 0, None, None, 0, 0, 0, v.handle, 0.0, None) == kv.KV_OK
+
+
 def test_unsupported_shapes_are_reported():
     L = kv.lib()
     fake = C.c_void_p(256)

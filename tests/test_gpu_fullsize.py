@@ -102,3 +102,75 @@ def test_repack_full_size_bit_exact(name, src, dst, lens):
         b = before[rc.src_table[s, :full]].reshape(full, 2, 16, row)[..., :run]
         assert np.array_equal(a, b)
         assert nb >= full
+
+
+def test_mixed_layout_full_size_sampled_rows():
+    """The mixed-layout case bench.py times (llama8b_tp_b128 under TP2 rank 0, every other sequence in
+    DP-layout blocks), sampled rows against the single-view oracle under each row's own view."""
+    w = wl.WORKLOADS["llama8b_tp_b128"]
+    mc = harness.build_mixed_case(w, 2, 0)
+    mc.run()
+    torch.cuda.synchronize()
+    got_all = bf16_bits_to_f64(host_u16(mc.out))
+    assert np.isfinite(got_all).all()
+    ps, ph = sample_pairs(mc.ctx, mc.views[0].n_q_local, 48, 4321)
+    pool, q, table = host_u16(mc.pool), host_u16(mc.q), mc.table_dev.cpu().numpy()
+    ids = mc.ids_dev.cpu().numpy()
+    for k, triple in enumerate([(1, 2, 0), (0, 2, 0)]):
+        sel = ids[ps] == k
+        assert sel.any()
+        view = oracle.View(geometry(w), *triple)
+        want = oracle.paged_decode_pairs(view, q, pool, table, mc.ctx, ps[sel], ph[sel])
+        err = np.abs(got_all[ps[sel], ph[sel]] - want)
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (triple, err.max(), err.mean())
+
+
+def test_prefill_bench_cases_sampled_rows():
+    """The first and the last prefill case of bench.py at full size: sampled query rows (first and last
+    tokens of sequences, query-tile and key-tile borders) against the oracle."""
+    w8 = wl.Workload("llama8b_recompute", 90, 32, 8, 128, 16, 8, "fixed", ())
+    for triple, ctx, ql in (((0, 1, 0), [4096] * 8, [4096] * 8), ((0, 1, 0), [8192] * 16, [512] * 16)):
+        pc = harness.build_prefill_case(w8, triple, ctx, ql)
+        pc.run()
+        torch.cuda.synchronize()
+        got_all = bf16_bits_to_f64(host_u16(pc.out))
+        assert np.isfinite(got_all).all()
+        q_off = wl.seq_offsets(pc.q_lens)
+        rng = np.random.default_rng(99)
+        rows = np.unique(np.concatenate([q_off[:-1], q_off[1:] - 1, q_off[:2] + 31, q_off[:2] + 32,
+                                         rng.integers(0, q_off[-1], size=12)]))[:24].astype(np.int64)
+        hql = pc.view.n_q_local
+        rq = np.repeat(rows, 2)
+        rh = np.tile(np.array([0, hql - 1], dtype=np.int32), len(rows))
+        view = oracle.View(geometry(w8), *triple)
+        want = oracle.paged_prefill_rows(view, host_u16(pc.q), host_u16(pc.pool), pc.table_dev.cpu().numpy(),
+                                         pc.ctx, q_off, rq, rh)
+        err = np.abs(got_all[rq, rh] - want)
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (triple, err.max(), err.mean())
+
+
+def test_linear_view_full_size_sampled_outputs():
+    """Llama-8B projections at full size (hidden 4096) on rank views, M = 64 and 256: every output of
+    a sample of batch rows against the fp64 product."""
+    from oracle import weights as ow
+    hq, hkv, d, hidden = 32, 8, 128, 4096
+    g = wl.generator(42, 1)
+    wq = wl.randn_bf16(((hq + 2 * hkv) * d, hidden), g)
+    wo = wl.randn_bf16((hidden, hq * d), g)
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+    dwq, dwo = dev(wq), dev(wo)
+    for M, m, r in ((64, 1, 0), (256, 2, 1), (100, 8, 7)):
+        x = wl.randn_bf16((M, hidden), g)
+        a = wl.randn_bf16((M, hq * d), g)
+        rows = np.unique(np.array([0, 1, 15, 16, 63, M // 2, M - 1]))
+        ov = ow.weight_view_fused_qkv(hq, hkv, d, hidden, r, m)
+        y = kv.kv_linear_view(dev(x), dwq, kv.kv_weight_view_fused_qkv(hq, hkv, d, hidden, r, m))
+        ov2 = ow.weight_view(1, r, m, hidden, hq * d)
+        xs = np.ascontiguousarray(a[:, ov2.col_start:ov2.col_start + ov2.col_count])
+        y2 = kv.kv_linear_view(dev(a)[:, ov2.col_start:ov2.col_start + ov2.col_count], dwo,
+                               kv.kv_weight_view_make(1, r, m, hidden, hq * d))
+        torch.cuda.synchronize()
+        for got, want, K in ((bf16_bits_to_f64(host_u16(y))[rows], ow.linear_view(x[rows], wq, ov), hidden),
+                             (bf16_bits_to_f64(host_u16(y2))[rows], ow.linear_view(xs[rows], wo, ov2), ov2.col_count)):
+            tol = np.abs(want) * 2.0 ** -8 + 2.0 * K * K * 2.0 ** -24 + 1e-6
+            assert np.isfinite(got).all() and (np.abs(got - want) <= tol).all(), (M, m, r, np.abs(got - want).max())

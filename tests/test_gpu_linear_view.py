@@ -87,29 +87,3 @@ def test_output_rows_outside_the_batch_are_untouched():
     assert (out[M:] == 7.0).all() and (out[:, hidden:] == 7.0).all()
     check(out[:M, :hidden].contiguous().cpu().view(torch.int16).numpy().view(np.uint16),
           ow.linear_view(x, w, ow.weight_view(0, 0, 1, hidden, kin)), kin, "padded out")
-
-
-def test_host_checks():
-    L = kv.lib()
-    fake = C.c_void_p(256)
-    v = kv.kv_weight_view_make(0, 1, 2, 256, 512)
-    assert (v.row_start[0], v.row_count[0], v.col_start, v.col_count) == (128, 128, 0, 512)
-    out = kv.kv_weight_view()
-    assert L.kv_weight_view_make(0, 2, 2, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
-    assert L.kv_weight_view_make(1, 0, 3, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
-    assert L.kv_weight_view_make(2, 0, 1, 256, 512, C.byref(out)) == kv.KV_ERR_INVALID_ARG
-    assert L.kv_linear_view(fake, 512, fake, 256, 512, None, fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG
-    assert L.kv_linear_view(fake, 512, fake, 200, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG  # view outside the weight
-    assert L.kv_linear_view(fake, 256, fake, 256, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG  # ldx < cols
-    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(v), fake, 64, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG   # ldy < rows
-    assert L.kv_linear_view(None, 512, fake, 256, 512, C.byref(v), fake, 128, 4, fake, 1 << 30, None) == kv.KV_ERR_INVALID_ARG
-    assert L.kv_linear_view(None, 512, None, 256, 512, C.byref(v), None, 128, 0, None, 0, None) == kv.KV_OK
-    odd = kv.kv_weight_view_make(1, 0, 8, 256, 512)      # 64 columns: not a whole 128-wide slab
-    assert L.kv_linear_view(fake, 64, fake, 256, 512, C.byref(odd), fake, 256, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED
-    big = kv.kv_weight_view_make(0, 0, 1, 256, 4096)     # few tiles, many slabs: the input dimension is split
-    need = L.kv_linear_view_workspace_bytes(C.byref(big), 8)
-    assert need > 0 and need % (8 * 256 * 4) == 0
-    assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, fake, need - 1, None) == kv.KV_ERR_WORKSPACE
-    assert L.kv_linear_view(fake, 4096, fake, 256, 4096, C.byref(big), fake, 256, 8, None, need, None) == kv.KV_ERR_INVALID_ARG
-    thin = kv.kv_weight_view_make(0, 0, 8, 256, 512)     # 32 rows: not a whole 64-row tile
-    assert L.kv_linear_view(fake, 512, fake, 256, 512, C.byref(thin), fake, 32, 4, fake, 1 << 30, None) == kv.KV_ERR_UNSUPPORTED

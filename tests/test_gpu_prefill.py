@@ -89,23 +89,3 @@ def test_long_prompt_sampled_rows():
         rh = np.tile(np.arange(hql, dtype=np.int32), len(rows))
         want = oracle.paged_prefill_rows(c.view, c.q, c.pool, c.table, c.ctx, c.q_off, rq, rh)
         check_close(got[rq, rh], want, f"long {triple}")
-
-
-def test_unsupported_and_invalid():
-    L = kv.lib()
-    import ctypes as C
-    fake = C.c_void_p(256)
-    v = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_DP, 1, 0)          # head_dim 64
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
-        == kv.KV_ERR_UNSUPPORTED
-    v = kv.kv_view_create(48, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)        # group of 6
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
-        == kv.KV_ERR_UNSUPPORTED
-    v = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 65, v.handle, 0.0, None) \
-        == kv.KV_ERR_INVALID_ARG                                         # max_q_len > max_ctx_len
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 3, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
-        == kv.KV_ERR_INVALID_ARG                                         # table too narrow
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, None, 1, 64, 8, v.handle, 0.0, None) \
-        == kv.KV_ERR_INVALID_ARG
-    assert L.paged_prefill_attn(None, None, None, 0, None, 0, None, None, 0, 0, 0, v.handle, 0.0, None) == kv.KV_OK
