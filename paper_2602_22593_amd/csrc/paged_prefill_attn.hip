@@ -117,21 +117,26 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         const int slot = tok - hb * v.block_tokens;
         return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot * token_stride_bytes;
     };
-    kv_u32x4 stage_k[2], stage_v[2];
-    auto fetch = [&](int tile) {
+    // Two register stages: tile t's pieces travel in stage t % 2, are issued two tiles ahead of
+    // their use and written to LDS one tile ahead, so a whole tile's arithmetic lies between a load
+    // and the first wait for it.  Tiles past the last are replaced by the last (loads stay
+    // unconditional, so every wait leaves exactly the younger stage in flight).
+    kv_u32x4 stage_k[2][2], stage_v[2][2];
+    auto fetch = [&](int stg, int tile) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const char* p = piece(tile, h);
-            stage_k[h] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(p));
-            stage_v[h] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(p + plane_bytes));
+            // ordinary (cached) loads: every query tile of the sequence reads these keys again
+            stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(p);
+            stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(p + plane_bytes);
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int stg, int buf) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int row = 16 * h + ld_row;
-            s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[h];
-            s_v[buf][row * 16 + ld_c] = stage_v[h];
+            s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[stg][h];
+            s_v[buf][row * 16 + ld_c] = stage_v[stg][h];
         }
     };
 
@@ -145,15 +150,16 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         for (int j = 0; j < 8; ++j) o[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    fetch(0);
-    stash(0);
+    const int last_tile = n_tiles - 1;
+    fetch(0, 0);
+    stash(0, 0);
     __syncthreads();
+    fetch(1, min(1, last_tile));
 
     const int k_row = 4 * (r & 3) + (r >> 2);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        if (tile + 1 < n_tiles) fetch(tile + 1);
-
+    constexpr float kLag = 8.0f;
+    const float lag_raw = kLag / a.scale_log2e;
+    auto compute = [&](int buf, int tile) {
         const int base = 32 * tile;
         if (base <= max_pos) {  // else every key of the tile lies after all of this wavefront's queries
             // ---- S^T = K q^T ------------------------------------------------------------------------
@@ -175,12 +181,17 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             bf16x8 pb[R];
 #pragma unroll
             for (int b = 0; b < R; ++b) {
+                // Scores stay in the products' own units; the scale is folded into the exponent.
+                // m[b] is a reference maximum that is allowed to lag behind the true running
+                // maximum by up to kLag in the exponent: weights then reach 2^kLag at most (exact in
+                // fp32 and in the bf16 operand alike), and the accumulators are rescaled only when
+                // some column's maximum has moved further than that -- rarely, after the first tiles.
                 float sv[8];
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float x = sacc[b][h][i] * a.scale_log2e;
+                        float x = sacc[b][h][i];
                         if (masked) x = (base + 16 * h + 4 * i + quad <= pos[b]) ? x : kNegInf;
                         sv[4 * h + i] = x;
                     }
@@ -188,19 +199,20 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // tile 0 holds key 0, which every query sees: the maximum is finite from then on
-                const float m_new = fmaxf(m[b], mx);
-                if (__builtin_amdgcn_ballot_w64(m_new != m[b]) != 0) {
-                    const float alpha = fast_exp2(m[b] - m_new);
+                // tile 0 holds key 0, which every query sees: the reference is finite from then on
+                if (__builtin_amdgcn_ballot_w64(mx > m[b] + lag_raw) != 0) {
+                    const float m_new = fmaxf(m[b], mx);
+                    const float alpha = fast_exp2((m[b] - m_new) * a.scale_log2e);
                     l[b] *= alpha;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) o[b][j] *= alpha;
                     m[b] = m_new;
                 }
+                const float neg_mc = -m[b] * a.scale_log2e;
                 float p[8], psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    p[u] = fast_exp2(sv[u] - m_new);
+                    p[u] = fast_exp2(__builtin_fmaf(sv[u], a.scale_log2e, neg_mc));
                     psum += p[u];
                 }
                 l[b] += psum;
@@ -230,7 +242,16 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             }
         }
 
-        if (tile + 1 < n_tiles) stash(buf ^ 1);
+    };
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        fetch(0, min(tile + 2, last_tile));
+        compute(0, tile);
+        stash(1, 1);
+        __syncthreads();
+        if (tile + 1 >= n_tiles) break;
+        fetch(1, min(tile + 3, last_tile));
+        compute(1, tile + 1);
+        stash(0, 0);
         __syncthreads();
     }
 
