@@ -1,0 +1,125 @@
+"""One decode step of one rank's attention sub-layer, composed from the library's entry points:
+QKV projection on the rank's weight view -> KV append through the rank's layout view -> paged
+decode attention -> output projection on the rank's weight view (partial sum).  Checked stage by
+stage against the oracle, and the paper's premise is checked on the GPU results themselves: the
+partial sums of the ranks of a TP group add up to what the unsharded (DP) engine computes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import LAYOUT_DP, LAYOUT_TP
+from oracle import weights as ow
+from paper_2602_22593_amd import binding as kv
+from paper_2602_22593_amd import workloads as wl
+
+from helpers import bf16_bits_to_f64, geometry
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+HQ, HKV, D, HIDDEN, B0 = 32, 8, 128, 512, 16
+
+
+def f64_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round to nearest even to bf16 (via fp32; the values here are far from fp32's own rounding ties)."""
+    u = a.astype(np.float32).view(np.uint32)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def dev(a):
+    return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def host(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def close(got_bits, want, rel, abs_, what):
+    got = bf16_bits_to_f64(got_bits)
+    assert np.isfinite(got).all(), what
+    bad = np.abs(got - want) > np.abs(want) * rel + abs_
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} off, worst {np.abs(got - want).max():.4g}"
+
+
+def run_rank(w, triple, m, r, x, wqkv, wo, ctx, K_old, V_old):
+    """Returns (qkv bits, attention bits, projected bits) of rank r computed on the GPU, each stage
+    checked against the oracle fed with the GPU's own previous stage (so errors do not compound)."""
+    view_o = oracle.View(geometry(w), *triple)
+    info = view_o.query()
+    view_g = kv.kv_view_create(HQ, HKV, D, B0, *triple)
+    hql, hl = info["n_q_local"], info["n_kv_local"]
+    # stage 1: fused QKV projection on the rank's rows of the full weight
+    wv_o, wv_g = ow.weight_view_fused_qkv(HQ, HKV, D, HIDDEN, r, m), kv.kv_weight_view_fused_qkv(HQ, HKV, D, HIDDEN, r, m)
+    qkv = kv.kv_linear_view(dev(x), dev(wqkv), wv_g)
+    torch.cuda.synchronize()
+    qkv_bits = host(qkv)
+    close(qkv_bits, ow.linear_view(x, wqkv, wv_o), 2.0 ** -8, 0.05, f"qkv {triple}")
+    q = qkv[:, :hql * D].reshape(-1, hql, D).contiguous()
+    k_new = qkv[:, hql * D:(hql + hl) * D].reshape(-1, hl, D).contiguous()
+    v_new = qkv[:, (hql + hl) * D:].reshape(-1, hl, D).contiguous()
+    # stage 2: the cache so far (scattered by the oracle), then the new token appended by the library
+    new_ctx = (ctx + 1).astype(np.int32)
+    perm = wl.shuffled_pool(int(wl.blocks_needed(new_ctx, info["block_tokens"]).sum()), 1.3,
+                            wl.generator(w.index, wl.SUB_PERM + r))
+    table, _ = wl.assign_blocks(new_ctx, info["block_tokens"], perm)
+    pool = wl.poisoned_pool(len(perm), info["block_bytes"] // 2)
+    off = wl.seq_offsets(ctx)
+    oracle.scatter(view_o, pool, table, ctx, off, K_old, V_old)
+    dpool = dev(pool)
+    kv.kv_append(dpool, view_g, k_new, v_new, torch.from_numpy(table).to(DEV), torch.from_numpy(ctx).to(DEV))
+    # the oracle's pool gets the same rows: the rank's slice of the GPU's own k_new / v_new
+    K_all = np.zeros((int(new_ctx.sum()), HKV, D), dtype=np.uint16)
+    V_all = np.zeros_like(K_all)
+    noff = wl.seq_offsets(new_ctx)
+    h0 = info["kv_head0"]
+    for s in range(len(ctx)):
+        K_all[noff[s]:noff[s] + ctx[s]] = K_old[off[s]:off[s + 1]]
+        V_all[noff[s]:noff[s] + ctx[s]] = V_old[off[s]:off[s + 1]]
+        K_all[noff[s] + ctx[s], h0:h0 + hl] = host(k_new)[s]
+        V_all[noff[s] + ctx[s], h0:h0 + hl] = host(v_new)[s]
+    pool_o = wl.poisoned_pool(len(perm), info["block_bytes"] // 2)
+    oracle.scatter(view_o, pool_o, table, new_ctx, noff, K_all, V_all)
+    torch.cuda.synchronize()
+    got_pool = host(dpool).reshape(pool_o.shape)
+    assert np.array_equal(got_pool, pool_o), f"append {triple}: pool differs from the oracle's scatter"
+    # stage 3: decode attention over the grown cache
+    attn = kv.paged_decode_attn(q, dpool, torch.from_numpy(table).to(DEV), torch.from_numpy(new_ctx).to(DEV),
+                                view_g, int(new_ctx.max()))
+    torch.cuda.synchronize()
+    attn_bits = host(attn)
+    want = oracle.paged_decode(view_o, host(q), pool_o, table, new_ctx)
+    err = np.abs(bf16_bits_to_f64(attn_bits) - want)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (triple, err.max(), err.mean())
+    # stage 4: output projection: the rank's columns of W^O times its slice of the attention output
+    wo_o, wo_g = ow.weight_view(1, r, m, HIDDEN, HQ * D), kv.kv_weight_view_make(1, r, m, HIDDEN, HQ * D)
+    a2 = attn.reshape(-1, hql * D)
+    y = kv.kv_linear_view(a2, dev(wo), wo_g)
+    torch.cuda.synchronize()
+    close(host(y), ow.linear_view(attn_bits.reshape(-1, hql * D), wo, wo_o), 2.0 ** -8, 0.02, f"wo {triple}")
+    return qkv_bits, attn_bits, host(y)
+
+
+def test_tp_ranks_reproduce_the_dp_engine():
+    w = wl.Workload("sublayer", 96, HQ, HKV, D, B0, 6, "x", ())
+    ctx = np.array([5, 40, 129, 0, 700, 63], dtype=np.int32)
+    g = wl.generator(w.index, wl.SUB_MISC)
+    x = wl.randn_bf16((len(ctx), HIDDEN), g)
+    # weights scaled so that q, k, v and the output stay O(1) like the cache contents
+    wqkv = f64_to_bf16_bits(bf16_bits_to_f64(wl.randn_bf16(((HQ + 2 * HKV) * D, HIDDEN), g)) / np.sqrt(HIDDEN))
+    wo = f64_to_bf16_bits(bf16_bits_to_f64(wl.randn_bf16((HIDDEN, HQ * D), g)) / np.sqrt(HQ * D))
+    K_old, V_old = wl.logical_kv(w, ctx)
+    _, attn_dp, y_dp = run_rank(w, (LAYOUT_DP, 1, 0), 1, 0, x, wqkv, wo, ctx, K_old, V_old)
+    for m in (2, 4):
+        total = np.zeros((len(ctx), HIDDEN))
+        for r in range(m):
+            _, attn_r, y_r = run_rank(w, (LAYOUT_TP, m, r), m, r, x, wqkv, wo, ctx, K_old, V_old)
+            # a rank's attention output is the DP engine's for the heads it owns (the same numbers up to
+            # the order in which the pieces of a sequence are merged: one bf16 ulp at most)
+            hql = HQ // m
+            a_r, a_dp = bf16_bits_to_f64(attn_r), bf16_bits_to_f64(attn_dp[:, r * hql:(r + 1) * hql])
+            assert (np.abs(a_r - a_dp) <= np.abs(a_dp) * 2.0 ** -7 + 1e-4).all(), (m, r)
+            total += bf16_bits_to_f64(y_r)
+        # sum of the ranks' bf16 partials vs the DP engine's single bf16 result: m + 1 roundings apart
+        want = bf16_bits_to_f64(y_dp)
+        assert (np.abs(total - want) <= np.abs(want) * 2.0 ** -6 + 0.02).all(), (m, np.abs(total - want).max())
