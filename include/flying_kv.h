@@ -277,7 +277,13 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
                        const kv_view* other_view, const int32_t* other_table,
                        int64_t other_stride, void* hip_stream);
 
-/* Tunables for experiments: "chunk_tokens" (split-KV granularity, 0 = automatic).
+/* Tunables for experiments and tests (process-wide; 0 = automatic for all of them):
+ *   "chunk_tokens"  split-KV granularity of the chunked decode kernels, a multiple of 64
+ *   "force_kernel"  decode kernel: 1 even split over resident wavefronts, 2 vector ALU, 3 chunked
+ *                   matrix-core (KV_ERR_UNSUPPORTED from the call if the shape is not served)
+ *   "waves_per_cu"  wavefronts per compute unit launched by the even-split kernel, a multiple of 4
+ *   "variant"       build variant of the even-split kernel: bit 0 K operands fetched directly
+ *                   instead of through LDS, bit 1 no register double buffering
  * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
 int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);

@@ -309,15 +309,12 @@ extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool,
     a.group_shift = 0;
     while ((1 << a.group_shift) < G) ++a.group_shift;
     hipStream_t st = (hipStream_t)hip_stream;
-    const int R = (int)kv_option_variant() == 1 ? 4 : 2;
+    constexpr int R = 2;  // 16-row blocks per wavefront (4 measured 2x slower: one wavefront per SIMD)
     const int tokens_per_wg = (64 * R) / G;
     const dim3 grid((unsigned)((max_q_len + tokens_per_wg - 1) / tokens_per_wg), (unsigned)view->n_kv_local,
                     (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_PREFILL, st);
-    if (R == 4)
-        hipLaunchKernelGGL(prefill_kernel<4>, grid, dim3(kThreads), 0, st, a);
-    else
-        hipLaunchKernelGGL(prefill_kernel<2>, grid, dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(prefill_kernel<R>, grid, dim3(kThreads), 0, st, a);
     kv_prof_end(KV_PROF_PREFILL, slot, st);
     return kv_record_hip_error(hipGetLastError(), "paged_prefill_attn launch");
 }

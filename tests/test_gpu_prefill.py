@@ -43,24 +43,19 @@ CTX = np.array([17, 64, 150, 300, 5, 33, 613, 96], dtype=np.int32)
 QLEN = np.array([17, 1, 40, 300, 0, 32, 77, 96], dtype=np.int32)   # whole prompt, decode, chunks, none
 
 
-@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("hq,hkv,triple", [
     (32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 2, 1)), (32, 8, (LAYOUT_TP, 8, 5)),
     (32, 8, (LAYOUT_DP, 4, 3)), (64, 8, (LAYOUT_TP, 8, 2)), (8, 8, (LAYOUT_TP, 2, 0)),
     (16, 8, (LAYOUT_DP, 1, 0)), (128, 8, (LAYOUT_TP, 4, 1))])
-def test_prefill_matches_oracle(hq, hkv, triple, variant):
+def test_prefill_matches_oracle(hq, hkv, triple):
     """Group sizes 1, 2, 4, 8 and 16; every layout; query lengths that are the whole context, one
     token, none, and chunks whose ends fall inside key tiles and query tiles; pool NaN-poisoned
     outside the valid tokens.  Every output row is compared."""
-    kv.kv_set_option("variant", variant)
-    try:
-        w = wl.Workload("prefill", 80 + hq // 8, hq, hkv, 128, 16, len(CTX), "x", ())
-        c = make_prefill_case(w, triple, CTX, QLEN)
-        want = oracle.paged_prefill(c.view, c.q, c.pool, c.table, c.ctx, c.q_off)
-        got = run_gpu(c, gpu_view(w, triple))
-        check_close(got, want, f"{hq}/{hkv} {triple} variant {variant}")
-    finally:
-        kv.kv_set_option("variant", 0)
+    w = wl.Workload("prefill", 80 + hq // 8, hq, hkv, 128, 16, len(CTX), "x", ())
+    c = make_prefill_case(w, triple, CTX, QLEN)
+    want = oracle.paged_prefill(c.view, c.q, c.pool, c.table, c.ctx, c.q_off)
+    got = run_gpu(c, gpu_view(w, triple))
+    check_close(got, want, f"{hq}/{hkv} {triple}")
 
 
 def test_one_query_token_per_sequence_is_decode():
