@@ -48,7 +48,7 @@ struct linear_args {
     float* part;            // [splits][M][Nl] fp32 when splits > 1
 };
 
-__global__ __launch_bounds__(kThreads, 4) void linear_view_kernel(linear_args p)
+__global__ __launch_bounds__(kThreads, 3) void linear_view_kernel(linear_args p)
 {
     // x slab in operand order: piece (kk, cb, quad, c) = x[16 cb + c][32 kk + 8 quad .. + 8) of the
     // step sits at ((kk * 4 + cb) * 4 + quad) * 16 + (c ^ (4 kk + quad)): a B operand is one
@@ -88,41 +88,73 @@ __global__ __launch_bounds__(kThreads, 4) void linear_view_kernel(linear_args p)
 #pragma unroll
     for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    kv_u32x4 a_cur[4], a_nxt[4], x_nxt[4];
-    auto fetch = [&](kv_u32x4 (&a)[4], int st) {
+    // Step k travels in register stage k % 2: its loads are issued during step k - 2 (as soon as
+    // that step's arithmetic has released the stage), its x pieces are written to LDS buffer k % 2
+    // at the end of step k - 1, its weights are used from the registers in step k.  The
+    // steady-state loop refills a stage in every step with unconditional loads (every wait then
+    // leaves exactly the younger stage in flight); the last two steps run without loads.
+    kv_u32x4 a_st[2][4], x_st[2][4];
+    auto fetch = [&](int stg, int st) {
         const int64_t off = (int64_t)st * (kSlab * 2);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-            a[kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase + off + kk * 64));
+            a_st[stg][kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase + off + kk * 64));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x_nxt[i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off);
+        for (int i = 0; i < 4; ++i) x_st[stg][i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off);
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int stg) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s_x[buf][xdst[i]] = x_nxt[i];
+        for (int i = 0; i < 4; ++i) s_x[stg][xdst[i]] = x_st[stg][i];
     };
-
-    if (step < last) {
-        fetch(a_cur, step);
-        stash(0);
-    }
-    __syncthreads();
-    for (int buf = 0; step < last; ++step, buf ^= 1) {
-        const bool more = step + 1 < last;
-        if (more) fetch(a_nxt, step + 1);
+    auto compute = [&](int stg) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
             for (int cb = 0; cb < kColBlocks; ++cb) {
-                const kv_u32x4 b = s_x[buf][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_cur[kk]), as_bf16x8(b), acc[cb], 0, 0, 0);
+                const kv_u32x4 b = s_x[stg][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_st[stg][kk]), as_bf16x8(b), acc[cb], 0, 0, 0);
             }
-        if (more) {
-            stash(buf ^ 1);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) a_cur[kk] = a_nxt[kk];
-        }
+    };
+
+    if (step < last) {
+        fetch(0, step);
+        fetch(1, min(step + 1, last - 1));
+        stash(0);
         __syncthreads();
+        int cur = 0;
+        for (;;) {
+            if (step + 2 >= last) break;
+            compute(0);
+            fetch(0, step + 2);
+            stash(1);
+            __syncthreads();
+            ++step;
+            if (step + 2 >= last) {
+                cur = 1;
+                break;
+            }
+            compute(1);
+            fetch(1, step + 2);
+            stash(0);
+            __syncthreads();
+            ++step;
+        }
+        // steps `step` (in stage cur, already in LDS) and possibly `step + 1` (other stage) remain
+        if (cur == 0) {
+            compute(0);
+            if (step + 1 < last) {
+                stash(1);
+                __syncthreads();
+                compute(1);
+            }
+        } else {
+            compute(1);
+            if (step + 1 < last) {
+                stash(0);
+                __syncthreads();
+                compute(0);
+            }
+        }
     }
 
     // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 wave + 4 quad + i]
