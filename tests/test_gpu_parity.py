@@ -203,6 +203,23 @@ def test_mixed_layouts_in_one_launch(p, r):
                 oracle.paged_decode(c1.view, c1.q, c1.pool, c1.table, c1.ctx), "one view")
 
 
+@pytest.mark.parametrize("batch", [2048, 2049])
+def test_batch_at_and_past_the_even_split_limit(batch):
+    """2048 sequences is the most the even-split kernel keeps in its LDS prefix table; one more and
+    the call is served by the chunked matrix-core kernel.  Short contexts (1..80 tokens, some empty),
+    every row compared."""
+    rng = np.random.default_rng(batch)
+    ctx = rng.integers(0, 81, size=batch).astype(np.int32)
+    ctx[:4] = [0, 1, 16, 80]
+    w = wl.Workload("bigbatch", 74, 32, 8, 128, 16, batch, "x", ())
+    triple = (LAYOUT_TP, 4, 2)
+    c = make_case(w, triple, ctx)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    got = run_gpu_decode(c, gpu_view(w, triple))
+    check_close(got, want, f"batch {batch}")
+    assert (got[ctx == 0] == 0).all()
+
+
 def test_explicit_scale_and_large_logits():
     """A scale of 1.0 (8x the default at d = 64) makes the softmax nearly one-hot: checks the
     running-max handling."""
