@@ -173,7 +173,7 @@ int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64
  * Other arguments as paged_decode_attn; no workspace is needed.  q_len[s] = 1 for every s is
  * paged_decode_attn.  Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, max_q_len >
  * max_ctx_len, block_table_stride too small), KV_ERR_UNSUPPORTED (head_dim != 128, group size
- * not a power of two <= 16, block capacity not a multiple of 16), KV_ERR_HIP.
+ * above 16, block capacity not a multiple of 16), KV_ERR_HIP.
  */
 int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
                        const int32_t* block_table, int64_t block_table_stride,

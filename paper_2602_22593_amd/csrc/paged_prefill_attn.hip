@@ -16,7 +16,8 @@
 //                                             pieces of V rows with byte permutes
 // so the accumulator layout of S^T is already the B layout of the second product and only the
 // running maximum crosses lanes.  Column c of row block b of wavefront w is row
-// rho = (w R + b) 16 + c of the tile: token rho / G, head rho % G.  The causal mask keeps
+// rho = (w R + b) 16 + c of the tile: token rho / Gp, head rho % Gp, Gp = G rounded up to a power
+// of two (rows with head >= G are padding).  The causal mask keeps
 // token t for a query at position pos iff t <= pos; since pos < ctx_len it also masks the slots
 // past the end of the sequence.
 #include "decode_common.h"
@@ -38,8 +39,8 @@ struct prefill_args {
     const int32_t* q_off;   // [batch + 1]
     kv_view_dev v;
     float scale_log2e;
-    int32_t group;          // G in {1, 2, 4, 8, 16}
-    int32_t group_shift;
+    int32_t group;          // G <= 16 query heads per KV head
+    int32_t group_shift;    // log2 of G rounded up to a power of two: rows per token in the tile
 };
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -76,11 +77,12 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 #pragma unroll
     for (int b = 0; b < R; ++b) {
         const int rho = (wave * R + b) * 16 + r;
-        const int jt = j0 + (rho >> a.group_shift), g = rho & (G - 1);
+        // a token takes 2^group_shift rows of the tile, the first G of which are its query heads
+        const int jt = j0 + (rho >> a.group_shift), g = rho & ((1 << a.group_shift) - 1);
         const int jc = min(jt, q_len - 1);
         pos[b] = first_pos + jc;
-        const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + g) * D;
-        orow[b] = jt < q_len ? row : -1;
+        const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + min(g, G - 1)) * D;
+        orow[b] = (jt < q_len && g < G) ? row : -1;
         const char* qrow = reinterpret_cast<const char*>(a.q + row) + quad * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -292,7 +294,7 @@ extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool,
     const int64_t need_cols = ((int64_t)max_ctx_len + view->block_tokens - 1) / view->block_tokens;
     if (block_table_stride < need_cols) return KV_ERR_INVALID_ARG;
     const int G = view->group;
-    if (view->geom.head_dim != D || view->block_tokens % 16 != 0 || G > 16 || (G & (G - 1)) != 0)
+    if (view->geom.head_dim != D || view->block_tokens % 16 != 0 || G > 16)
         return KV_ERR_UNSUPPORTED;
     if (batch > 65535 || view->n_kv_local > 65535) return KV_ERR_UNSUPPORTED;
     prefill_args a;
@@ -310,7 +312,7 @@ extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool,
     while ((1 << a.group_shift) < G) ++a.group_shift;
     hipStream_t st = (hipStream_t)hip_stream;
     constexpr int R = 2;  // 16-row blocks per wavefront (4 measured 2x slower: one wavefront per SIMD)
-    const int tokens_per_wg = (64 * R) / G;
+    const int tokens_per_wg = (64 * R) >> a.group_shift;
     const dim3 grid((unsigned)((max_q_len + tokens_per_wg - 1) / tokens_per_wg), (unsigned)view->n_kv_local,
                     (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_PREFILL, st);

@@ -202,7 +202,7 @@ def test_prefill_entry_point_checks_without_a_gpu():
     v = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_DP, 1, 0)          # head_dim 64
     assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
         == kv.KV_ERR_UNSUPPORTED
-    v = kv.kv_view_create(48, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)        # group of 6
+    v = kv.kv_view_create(8 * 24, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)    # group of 24
     assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
         == kv.KV_ERR_UNSUPPORTED
     v = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)

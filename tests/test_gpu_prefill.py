@@ -46,9 +46,9 @@ QLEN = np.array([17, 1, 40, 300, 0, 32, 77, 96], dtype=np.int32)   # whole promp
 @pytest.mark.parametrize("hq,hkv,triple", [
     (32, 8, (LAYOUT_DP, 1, 0)), (32, 8, (LAYOUT_TP, 2, 1)), (32, 8, (LAYOUT_TP, 8, 5)),
     (32, 8, (LAYOUT_DP, 4, 3)), (64, 8, (LAYOUT_TP, 8, 2)), (8, 8, (LAYOUT_TP, 2, 0)),
-    (16, 8, (LAYOUT_DP, 1, 0)), (128, 8, (LAYOUT_TP, 4, 1))])
+    (16, 8, (LAYOUT_DP, 1, 0)), (128, 8, (LAYOUT_TP, 4, 1)), (48, 8, (LAYOUT_TP, 2, 1)), (24, 2, (LAYOUT_DP, 1, 0))])
 def test_prefill_matches_oracle(hq, hkv, triple):
-    """Group sizes 1, 2, 4, 8 and 16; every layout; query lengths that are the whole context, one
+    """Group sizes 1, 2, 4, 6, 8, 12 and 16; every layout; query lengths that are the whole context, one
     token, none, and chunks whose ends fall inside key tiles and query tiles; pool NaN-poisoned
     outside the valid tokens.  Every output row is compared."""
     w = wl.Workload("prefill", 80 + hq // 8, hq, hkv, 128, 16, len(CTX), "x", ())
