@@ -222,7 +222,9 @@ def main():
         w8 = wl.Workload("llama8b_recompute", 90, 32, 8, 128, 16, 8, "fixed", ())
         for label, tr, ctx, ql in (("8 prompts of 4096 tokens, whole", (0, 1, 0), [4096] * 8, [4096] * 8),
                                    ("8 prompts of 4096 tokens, whole", (1, 2, 0), [4096] * 8, [4096] * 8),
-                                   ("16 chunks of 512 tokens on 8192 cached", (0, 1, 0), [8192] * 16, [512] * 16)):
+                                   ("16 chunks of 512 tokens on 8192 cached", (0, 1, 0), [8192] * 16, [512] * 16),
+                                   ("1 chunk of 512 tokens on 131072 cached (key range split over workgroups)",
+                                    (0, 1, 0), [131072], [512])):
             pc = harness.build_prefill_case(w8, tr, ctx, ql)
             kv.kv_profile_enable(True)
             ms = harness.time_calls(pc.run, 10, 2)

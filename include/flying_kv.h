@@ -169,16 +169,22 @@ int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64
  *   q, out       device, bf16 [total_q][n_q_local][head_dim], total_q = q_offsets[batch]
  *   q_offsets    device, int32 [batch + 1], non-decreasing, q_offsets[0] = 0
  *   ctx_lens     device, int32 [batch]; q_len[s] <= ctx_lens[s] <= max_ctx_len is a precondition
+ *   total_q      q_offsets[batch], known to the host (the number of rows of q and out)
  *   max_q_len    host upper bound of q_len (sizes the launch)
- * Other arguments as paged_decode_attn; no workspace is needed.  q_len[s] = 1 for every s is
- * paged_decode_attn.  Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, max_q_len >
+ *   workspace    device scratch of at least paged_prefill_attn_workspace_bytes(...) bytes (0 when
+ *                the launch fills the chip without splitting the key range: null is then
+ *                accepted), 256-byte aligned; contents need not be initialised
+ * Other arguments as paged_decode_attn.  q_len[s] = 1 for every s is paged_decode_attn.  Errors: KV_ERR_INVALID_ARG (null pointers, negative sizes, max_q_len >
  * max_ctx_len, block_table_stride too small), KV_ERR_UNSUPPORTED (head_dim != 128, group size
- * above 16, block capacity not a multiple of 16), KV_ERR_HIP.
+ * above 16, block capacity not a multiple of 16), KV_ERR_WORKSPACE, KV_ERR_HIP.
  */
+size_t paged_prefill_attn_workspace_bytes(const kv_view* view, int batch, int64_t total_q,
+                                          int max_ctx_len, int max_q_len);
 int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
                        const int32_t* block_table, int64_t block_table_stride,
-                       const int32_t* ctx_lens, const int32_t* q_offsets, int batch, int max_ctx_len,
-                       int max_q_len, const kv_view* view, float scale, void* hip_stream);
+                       const int32_t* ctx_lens, const int32_t* q_offsets, int batch, int64_t total_q,
+                       int max_ctx_len, int max_q_len, const kv_view* view, float scale,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Weight shard views (Model Weights Manager, Sec. 4.1; Eq. 1: W_active^(r) = View(W_full, dim, r,

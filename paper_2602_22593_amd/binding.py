@@ -59,8 +59,10 @@ def lib() -> C.CDLL:
                                     vp, C.c_size_t, vp]
     L.paged_decode_attn_mixed.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, vp, C.c_int,
                                           C.c_float, vp, C.c_size_t, vp]
-    L.paged_prefill_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, C.c_int, vp,
-                                     C.c_float, vp]
+    L.paged_prefill_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, i64, C.c_int, C.c_int, vp,
+                                     C.c_float, vp, C.c_size_t, vp]
+    L.paged_prefill_attn_workspace_bytes.argtypes = [vp, C.c_int, i64, C.c_int, C.c_int]
+    L.paged_prefill_attn_workspace_bytes.restype = C.c_size_t
     L.kv_weight_view_make.argtypes = [C.c_int, C.c_int, C.c_int, i64, i64, vp]
     L.kv_weight_view_fused_qkv.argtypes = [vp, i64, C.c_int, C.c_int, vp]
     L.kv_linear_view.argtypes = [vp, i64, vp, i64, i64, vp, vp, i64, C.c_int, vp, C.c_size_t, vp]
@@ -235,7 +237,7 @@ def paged_decode_attn_mixed(q: torch.Tensor, kv_pool: torch.Tensor, block_table:
 def paged_prefill_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch.Tensor,
                        ctx_lens: torch.Tensor, q_offsets: torch.Tensor, view: KVView, max_ctx_len: int,
                        max_q_len: int, out: Optional[torch.Tensor] = None, scale: float = 0.0,
-                       stream=None) -> torch.Tensor:
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """Causal attention of each sequence's last q_len tokens over its cached tokens, through ``view``.
 
     q: bf16 [total_q][n_q_local][head_dim]; q_offsets: int32 [batch + 1] (device); the K/V of the
@@ -251,11 +253,17 @@ def paged_prefill_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torc
     if block_table.dim() != 2 or block_table.shape[0] != batch:
         raise ValueError("block_table must be [batch][max_blocks]")
     n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // view.block_bytes
+    total_q = int(q.shape[0])
+    need = int(lib().paged_prefill_attn_workspace_bytes(view.handle, batch, total_q, int(max_ctx_len),
+                                                        int(max_q_len)))
+    if workspace is None:
+        workspace = _workspace(q.device, need)
     rc = lib().paged_prefill_attn(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"), n_pool_blocks,
         _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
         _dev(ctx_lens, (torch.int32,), "ctx_lens"), _dev(q_offsets, (torch.int32,), "q_offsets"), batch,
-        int(max_ctx_len), int(max_q_len), view.handle, float(scale), _stream_ptr(stream))
+        total_q, int(max_ctx_len), int(max_q_len), view.handle, float(scale),
+        _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream_ptr(stream))
     _check(rc, "paged_prefill_attn")
     return out
 

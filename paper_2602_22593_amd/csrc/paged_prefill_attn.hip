@@ -41,6 +41,10 @@ struct prefill_args {
     float scale_log2e;
     int32_t group;          // G <= 16 query heads per KV head
     int32_t group_shift;    // log2 of G rounded up to a power of two: rows per token in the tile
+    int32_t splits;         // workgroups sharing the key range of one query tile
+    int64_t rows;           // total_q * n_q_local: rows of the partial arrays
+    float* part_o;          // [splits][rows][128] un-normalised sums, when splits > 1
+    float* part_ml;         // [splits][rows][2]   (reference maximum in score units, sum of weights)
 };
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -64,11 +68,16 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const int q0 = a.q_off[s];
     const int q_len = a.q_off[s + 1] - q0;
     // longest tiles first: the last query tile of a sequence sees the most keys
-    const int j0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * tokens_per_wg;
+    const int split = (int)blockIdx.x % a.splits;
+    const int j0 = ((int)gridDim.x / a.splits - 1 - (int)blockIdx.x / a.splits) * tokens_per_wg;
     if (j0 >= q_len || n <= 0) return;
     const int first_pos = n - q_len;                         // position of the sequence's query 0
     const int j_last = min(j0 + tokens_per_wg, q_len) - 1;   // last query token of this tile
-    const int n_tiles = ((first_pos + j_last) >> 5) + 1;     // key tiles 0 .. n_tiles - 1
+    const int all_tiles = ((first_pos + j_last) >> 5) + 1;   // key tiles 0 .. all_tiles - 1 of the query tile
+    // this workgroup's share of them: [t_begin, n_tiles)
+    const int per_split = (all_tiles + a.splits - 1) / a.splits;
+    const int t_begin = split * per_split;
+    const int n_tiles = min(all_tiles, t_begin + per_split);
 
     // ---- this lane's query rows (B operands), one per row block --------------------------------
     bf16x8 qb[R][4];
@@ -153,10 +162,12 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     }
 
     const int last_tile = n_tiles - 1;
-    fetch(0, 0);
-    stash(0, 0);
-    __syncthreads();
-    fetch(1, min(1, last_tile));
+    if (t_begin < n_tiles) {
+        fetch(0, t_begin);
+        stash(0, 0);
+        __syncthreads();
+        fetch(1, min(t_begin + 1, last_tile));
+    }
 
     const int k_row = 4 * (r & 3) + (r >> 2);
     constexpr float kLag = 8.0f;
@@ -201,7 +212,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // tile 0 holds key 0, which every query sees: the reference is finite from then on
+                // (with the key range split, a column may have seen no valid key yet: m = -inf)
                 if (__builtin_amdgcn_ballot_w64(mx > m[b] + lag_raw) != 0) {
                     const float m_new = fmaxf(m[b], mx);
                     const float alpha = fast_exp2((m[b] - m_new) * a.scale_log2e);
@@ -210,7 +221,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                     for (int j = 0; j < 8; ++j) o[b][j] *= alpha;
                     m[b] = m_new;
                 }
-                const float neg_mc = -m[b] * a.scale_log2e;
+                const float neg_mc = (m[b] == kNegInf) ? 0.f : -m[b] * a.scale_log2e;
                 float p[8], psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
@@ -245,7 +256,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         }
 
     };
-    for (int tile = 0; tile < n_tiles; tile += 2) {
+    for (int tile = t_begin; tile < n_tiles; tile += 2) {
         fetch(0, min(tile + 2, last_tile));
         compute(0, tile);
         stash(1, 1);
@@ -263,7 +274,20 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         float lt = l[b];
         lt += __shfl_xor(lt, 16);
         lt += __shfl_xor(lt, 32);
-        if (orow[b] >= 0) {
+        if (orow[b] >= 0 && a.splits > 1) {
+            // partial of this key range: row = index of the output row
+            const int64_t rec = (int64_t)split * a.rows + orow[b] / D;
+            float* dst = a.part_o + rec * D + 32 * quad;
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                *reinterpret_cast<f32x4*>(dst + 8 * ii) = f32x4{o[b][0][ii], o[b][1][ii], o[b][2][ii], o[b][3][ii]};
+                *reinterpret_cast<f32x4*>(dst + 8 * ii + 4) = f32x4{o[b][4][ii], o[b][5][ii], o[b][6][ii], o[b][7][ii]};
+            }
+            if (quad == 0) {
+                a.part_ml[rec * 2 + 0] = m[b];
+                a.part_ml[rec * 2 + 1] = lt;
+            }
+        } else if (orow[b] >= 0) {
             const float inv = 1.0f / lt;
             uint16_t* dst = a.out + orow[b] + 32 * quad;
 #pragma unroll
@@ -278,18 +302,73 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     }
 }
 
+// out[row] = sum_z o_z 2^((m_z - M) c) / sum_z l_z 2^((m_z - M) c), M = max_z m_z; a split that saw
+// no valid key for the row has l = 0 and is skipped.  32 lanes per row, 4 columns each.
+__global__ __launch_bounds__(256) void prefill_merge_kernel(prefill_args a)
+{
+    const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int cg = threadIdx.x & 31;
+    if (row >= a.rows) return;
+    float mm = kNegInf;
+    for (int z = 0; z < a.splits; ++z) {
+        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)z * a.rows + row) * 2);
+        if (ml.y > 0.f) mm = fmaxf(mm, ml.x);
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float lt = 0.f;
+    for (int z = 0; z < a.splits; ++z) {
+        const int64_t rec = (int64_t)z * a.rows + row;
+        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
+        if (!(ml.y > 0.f)) continue;
+        const float w = fast_exp2((ml.x - mm) * a.scale_log2e);
+        lt += ml.y * w;
+        acc += *reinterpret_cast<const f32x4*>(a.part_o + rec * D + cg * 4) * w;
+    }
+    const float inv = 1.0f / lt;   // every query sees at least key 0
+    uint2 pk;
+    pk.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+    pk.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+    *reinterpret_cast<uint2*>(a.out + row * D + cg * 4) = pk;
+}
+
+constexpr int kRowBlocks = 2;  // 16-row blocks per wavefront (4 measured 2x slower: one wavefront per SIMD)
+
+// Workgroups sharing the key range of a query tile: only when the launch would otherwise leave
+// compute units idle (few sequences, few query tokens, long contexts); at least 16 key tiles each.
+int prefill_splits(const kv_view* view, int batch, int max_ctx_len, int max_q_len)
+{
+    int shift = 0;
+    while ((1 << shift) < view->group) ++shift;
+    const int tokens_per_wg = (64 * kRowBlocks) >> shift;
+    const int64_t wgs = (int64_t)((max_q_len + tokens_per_wg - 1) / tokens_per_wg) * view->n_kv_local * batch;
+    if (wgs >= 512) return 1;
+    int s = (int)((768 + wgs - 1) / wgs);
+    const int most = max_ctx_len / (32 * 16);
+    if (s > most) s = most;
+    if (s > 16) s = 16;
+    return s < 1 ? 1 : s;
+}
+
 }  // namespace
+
+extern "C" size_t paged_prefill_attn_workspace_bytes(const kv_view* view, int batch, int64_t total_q,
+                                                     int max_ctx_len, int max_q_len)
+{
+    if (!kv_view_ok(view) || batch <= 0 || total_q <= 0 || max_ctx_len <= 0 || max_q_len <= 0) return 0;
+    const int s = prefill_splits(view, batch, max_ctx_len, max_q_len);
+    return s > 1 ? (size_t)s * total_q * view->n_q_local * (D + 2) * 4 : 0;
+}
 
 extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
                                   const int32_t* block_table, int64_t block_table_stride,
                                   const int32_t* ctx_lens, const int32_t* q_offsets, int batch,
-                                  int max_ctx_len, int max_q_len, const kv_view* view, float scale,
-                                  void* hip_stream)
+                                  int64_t total_q, int max_ctx_len, int max_q_len, const kv_view* view,
+                                  float scale, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (!kv_view_ok(view) || batch < 0 || max_ctx_len < 0 || max_q_len < 0 || n_pool_blocks < 0 ||
-        block_table_stride < 0 || max_q_len > max_ctx_len)
+    if (!kv_view_ok(view) || batch < 0 || total_q < 0 || max_ctx_len < 0 || max_q_len < 0 ||
+        n_pool_blocks < 0 || block_table_stride < 0 || max_q_len > max_ctx_len)
         return KV_ERR_INVALID_ARG;
-    if (batch == 0 || max_q_len == 0) return KV_OK;
+    if (batch == 0 || max_q_len == 0 || total_q == 0) return KV_OK;
     if (!q || !out || !ctx_lens || !q_offsets || !kv_pool || !block_table) return KV_ERR_INVALID_ARG;
     const int64_t need_cols = ((int64_t)max_ctx_len + view->block_tokens - 1) / view->block_tokens;
     if (block_table_stride < need_cols) return KV_ERR_INVALID_ARG;
@@ -311,12 +390,26 @@ extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool,
     a.group_shift = 0;
     while ((1 << a.group_shift) < G) ++a.group_shift;
     hipStream_t st = (hipStream_t)hip_stream;
-    constexpr int R = 2;  // 16-row blocks per wavefront (4 measured 2x slower: one wavefront per SIMD)
+    constexpr int R = kRowBlocks;
+    a.splits = prefill_splits(view, batch, max_ctx_len, max_q_len);
+    a.rows = total_q * view->n_q_local;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+    if (a.splits > 1) {
+        const size_t need = (size_t)a.splits * a.rows * (D + 2) * 4;
+        if (!workspace || ((uintptr_t)workspace & 255u)) return KV_ERR_INVALID_ARG;
+        if (workspace_bytes < need) return KV_ERR_WORKSPACE;
+        a.part_o = (float*)workspace;
+        a.part_ml = a.part_o + (size_t)a.splits * a.rows * D;
+    }
     const int tokens_per_wg = (64 * R) >> a.group_shift;
-    const dim3 grid((unsigned)((max_q_len + tokens_per_wg - 1) / tokens_per_wg), (unsigned)view->n_kv_local,
-                    (unsigned)batch);
+    const int64_t q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
+    if (q_tiles * a.splits > 0x7fffffff) return KV_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(q_tiles * a.splits), (unsigned)view->n_kv_local, (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_PREFILL, st);
     hipLaunchKernelGGL(prefill_kernel<R>, grid, dim3(kThreads), 0, st, a);
+    if (a.splits > 1)
+        hipLaunchKernelGGL(prefill_merge_kernel, dim3((unsigned)((a.rows + 7) / 8)), dim3(256), 0, st, a);
     kv_prof_end(KV_PROF_PREFILL, slot, st);
     return kv_record_hip_error(hipGetLastError(), "paged_prefill_attn launch");
 }

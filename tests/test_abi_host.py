@@ -200,19 +200,19 @@ def test_prefill_entry_point_checks_without_a_gpu():
     L = kv.lib()
     fake = C.c_void_p(256)
     v = kv.kv_view_create(8, 2, 64, 16, kv.KV_LAYOUT_DP, 1, 0)          # head_dim 64
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 8, 64, 8, v.handle, 0.0, fake, 1 << 30, None) \
         == kv.KV_ERR_UNSUPPORTED
     v = kv.kv_view_create(8 * 24, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)    # group of 24
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 8, 64, 8, v.handle, 0.0, fake, 1 << 30, None) \
         == kv.KV_ERR_UNSUPPORTED
     v = kv.kv_view_create(32, 8, 128, 16, kv.KV_LAYOUT_DP, 1, 0)
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 64, 65, v.handle, 0.0, None) \
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, fake, 1, 8, 64, 65, v.handle, 0.0, fake, 1 << 30, None) \
         == kv.KV_ERR_INVALID_ARG                                         # max_q_len > max_ctx_len
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 3, fake, fake, 1, 64, 8, v.handle, 0.0, None) \
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 3, fake, fake, 1, 8, 64, 8, v.handle, 0.0, fake, 1 << 30, None) \
         == kv.KV_ERR_INVALID_ARG                                         # table too narrow
-    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, None, 1, 64, 8, v.handle, 0.0, None) \
+    assert L.paged_prefill_attn(fake, fake, fake, 10, fake, 64, fake, None, 1, 8, 64, 8, v.handle, 0.0, fake, 1 << 30, None) \
         == kv.KV_ERR_INVALID_ARG
-    assert L.paged_prefill_attn(None, None, None, 0, None, 0, None, None, 0, 0, 0, v.handle, 0.0, None) == kv.KV_OK
+    assert L.paged_prefill_attn(None, None, None, 0, None, 0, None, None, 0, 0, 0, 0, v.handle, 0.0, None, 0, None) == kv.KV_OK
 
 
 def test_unsupported_shapes_are_reported():

@@ -68,6 +68,34 @@ def test_one_query_token_per_sequence_is_decode():
     check_close(got, want, "q_len 1")
 
 
+@pytest.mark.parametrize("triple", [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 4, 1)])
+def test_short_chunks_on_long_contexts_split_the_key_range(triple):
+    """Two sequences, a few dozen new tokens each on thousands of cached ones: too few query tiles
+    to fill the chip, so the library cuts each tile's key range over several workgroups and merges
+    their partial results (the workspace path).  Includes splits that see no key at all for the
+    early rows of a tile.  Every row compared; the workspace starts as garbage."""
+    w = wl.Workload("prefill_split", 87, 32, 8, 128, 16, 2, "x", ())
+    ctx, qlen = np.array([9000, 3000], dtype=np.int32), np.array([70, 33], dtype=np.int32)
+    c = make_prefill_case(w, triple, ctx, qlen)
+    view = gpu_view(w, triple)
+    need = kv.lib().paged_prefill_attn_workspace_bytes(view.handle, 2, int(qlen.sum()), 9000, 70)
+    assert need > 0
+    ws = torch.full((need,), 0x7F, dtype=torch.uint8, device=DEV)
+    out = kv.paged_prefill_attn(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                                torch.from_numpy(c.ctx).to(DEV), torch.from_numpy(c.q_off.astype(np.int32)).to(DEV),
+                                view, 9000, 70, workspace=ws)
+    torch.cuda.synchronize()
+    got = bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
+    want = oracle.paged_prefill(c.view, c.q, c.pool, c.table, c.ctx, c.q_off)
+    check_close(got, want, f"split {triple}")
+    # too small a workspace is reported, not overrun
+    import ctypes as C
+    rc = kv.lib().paged_prefill_attn(C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 10, C.c_void_p(256), 1024,
+                                     C.c_void_p(256), C.c_void_p(256), 2, int(qlen.sum()), 9000, 70, view.handle,
+                                     0.0, C.c_void_p(256), need - 1, None)
+    assert rc == kv.KV_ERR_WORKSPACE
+
+
 def test_long_prompt_sampled_rows():
     """A 4096-token prompt prefilled whole next to a 1000-token chunk on a 5000-token context:
     many query tiles per sequence, the oracle on sampled rows (first, last, tile borders)."""
