@@ -289,7 +289,9 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
  *                   matrix-core (KV_ERR_UNSUPPORTED from the call if the shape is not served)
  *   "waves_per_cu"  wavefronts per compute unit launched by the even-split kernel, a multiple of 4
  *   "variant"       build variant of the even-split kernel: bit 0 K operands fetched directly
- *                   instead of through LDS, bit 1 no register double buffering
+ *                   instead of through LDS, bit 1 no register double buffering (both for the
+ *                   one-head-per-wavefront kernel), bit 2 one KV head per wavefront even where
+ *                   several adjacent heads per wavefront are possible
  * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
 int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);

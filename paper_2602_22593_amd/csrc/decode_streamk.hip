@@ -193,20 +193,22 @@ __device__ __forceinline__ void compute_tile(const tile_regs& t, const bf16x8 (&
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-template <int KMODE, int PIPE, bool MIXED>
-__global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kernel(kv_streamk_args a)
-{
-    __shared__ kv_u32x4 s_kstage[KMODE == 1 ? kSkWaves * 512 : 1];
-    __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
-    __shared__ int32_t s_ctx[kMaxBatch];
-    __shared__ int32_t s_wsum[kSkWaves];
+// Where a wavefront's share starts: tiles [x0, x1) of the flattened batch, the first one being
+// tile `tile` of pair `pair` of sequence `s` (which has tiles_s tiles per pair); w numbers the
+// wavefront.
+struct split_pos {
+    int x0, x1, s, tiles_s, pair, tile, w;
+};
 
+// Common start of the even-split kernels (whole workgroup): exclusive prefix sum of the tiles
+// (2^TSHIFT tokens) per sequence into s_prefix, context lengths into s_ctx, then this
+// wavefront's share and the position of its first tile.  False: the wavefront has no tiles.
+template <int TSHIFT>
+__device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pairs, int32_t* s_prefix,
+                                               int32_t* s_ctx, int32_t* s_wsum, split_pos& sp)
+{
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
-    const kv_view_dev& v = a.v;
-    const int Hl = v.n_kv_local, G = a.group;
-
-    // ---- exclusive prefix sum of tiles per sequence (whole workgroup) --------------------------
     {
         const int per = (a.batch + kSkThreads - 1) / kSkThreads;
         const int s0 = tid * per;
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
             if (s < a.batch) {
                 const int c = a.ctx_lens[s];
                 s_ctx[s] = c;
-                local += (c + 31) >> 5;
+                local += (c + (1 << TSHIFT) - 1) >> TSHIFT;
             }
         }
         int incl = local;
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
             const int s = s0 + k;
             if (s < a.batch) {
                 s_prefix[s] = run;
-                run += (s_ctx[s] + 31) >> 5;
+                run += (s_ctx[s] + (1 << TSHIFT) - 1) >> TSHIFT;
             }
         }
         if (tid == kSkThreads - 1) s_prefix[a.batch] = before + incl;
@@ -244,31 +246,46 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
             for (int k = tid; k <= a.batch; k += kSkThreads) a.prefix_out[k] = s_prefix[k];
     }
 
-    // ---- this wavefront's share ---------------------------------------------------------------
-    const int total = uniform(s_prefix[a.batch]) * Hl;
+    const int total = uniform(s_prefix[a.batch]) * pairs;
     const int tpw = (total + a.n_waves - 1) / a.n_waves;
-    const int w = blockIdx.x * kSkWaves + wave;
-    int x0 = w * tpw;
-    const int x1 = min(x0 + tpw, total);
-    if (x0 >= x1) return;
+    sp.w = blockIdx.x * kSkWaves + wave;
+    sp.x0 = sp.w * tpw;
+    sp.x1 = min(sp.x0 + tpw, total);
+    if (sp.x0 >= sp.x1) return false;
 
-    // sequence holding tile x0: largest s with prefix[s] * Hl <= x0
-    int s;
+    // sequence holding tile x0: largest s with prefix[s] * pairs <= x0
     {
         int lo = 0, hi = a.batch;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (uniform(s_prefix[mid]) * Hl <= x0) lo = mid; else hi = mid;
+            if (uniform(s_prefix[mid]) * pairs <= sp.x0) lo = mid; else hi = mid;
         }
-        s = lo;
+        sp.s = lo;
     }
-    int tiles_s = uniform(s_prefix[s + 1]) - uniform(s_prefix[s]);
-    int hl, tile;
-    {
-        const int rem = x0 - uniform(s_prefix[s]) * Hl;
-        hl = rem / tiles_s;
-        tile = rem - hl * tiles_s;
-    }
+    sp.tiles_s = uniform(s_prefix[sp.s + 1]) - uniform(s_prefix[sp.s]);
+    const int rem = sp.x0 - uniform(s_prefix[sp.s]) * pairs;
+    sp.pair = rem / sp.tiles_s;
+    sp.tile = rem - sp.pair * sp.tiles_s;
+    return true;
+}
+
+template <int KMODE, int PIPE, bool MIXED>
+__global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kernel(kv_streamk_args a)
+{
+    __shared__ kv_u32x4 s_kstage[KMODE == 1 ? kSkWaves * 512 : 1];
+    __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
+    __shared__ int32_t s_ctx[kMaxBatch];
+    __shared__ int32_t s_wsum[kSkWaves];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const kv_view_dev& v = a.v;
+    const int Hl = v.n_kv_local, G = a.group;
+
+    split_pos sp;
+    if (!split_prologue<5>(a, Hl, s_prefix, s_ctx, s_wsum, sp)) return;
+    int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hl = sp.pair, tile = sp.tile;
+    const int x1 = sp.x1, w = sp.w;
 
     lane_consts lc;
     lc.r = lane & 15;
@@ -428,6 +445,305 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
     }
 }
 
+// ---- several adjacent KV heads per wavefront ----------------------------------------------------
+// In a block whose token rows hold several local KV heads, a wavefront that reads one head
+// touches 256 bytes per token; measured on pure-read probes that pattern streams 10-12 % slower
+// than rows of 512 or 1024 bytes.  This variant gives a wavefront HPW = 2 or 4 adjacent heads: a
+// pair is (sequence, head group), its HPW * G <= 16 query rows fill the 16 columns of the B
+// operand that the one-head kernel pads, and a tile is 2 * TG tokens, TG = 16 / HPW.
+//
+// The 16 A rows of the score product are (head a, token t) combinations of one group of TG tokens,
+// row = a * TG + t; the B operand holds all 16 query rows, so S^T[(a, t)][(b, g)] is a score only
+// where a == b.  In the C layout lane (col, quad) holds rows 4 quad + i: head a = row / TG is
+// fixed per lane, so a lane either owns four tokens of its own column (a == b) or only cross
+// products, which it masks to -inf.  The masked S^T is again the B operand of the second product,
+// whose contraction index 4 quad + j = a * TG + t runs over heads as well as tokens: the A operand
+// takes V rows of head a for index (a, t), and the zeros of P remove the other heads' terms.  One
+// accumulator O^T[e][col] therefore serves all heads of the group, and a column's running maximum
+// lives in the lanes that own it (HPW = 4: one lane; HPW = 2: two lanes 16 apart).
+typedef short bf16x4_bits __attribute__((ext_vector_type(4)));
+
+struct wide_tile {
+    kv_u32x4 k[8];     // K rows as they lie in memory, 1 KiB per load instruction
+    kv_u32x4 v[2][4];  // [group][j]: piece r of the V row for contraction index 4 quad + j
+};
+
+struct wide_lane {
+    int r, quad;
+    int ktok, kcol;   // K loads: token within an instruction's tokens, byte offset inside the token row
+    int vtok, vcol;   // V loads: first token of this lane within a group, byte offset inside the row
+    int krow;         // row of the K staging buffer holding A row r of group 0
+    bool mine;        // this lane's rows of S^T belong to its own column
+    int src;          // a lane owning this lane's column (source of the rescale factor)
+};
+
+struct wide_state {
+    float m, l;   // m: reference maximum of the column (owners; 0 in other lanes), may lag the true one
+    f32x4 o[8];   // o[e][i] = O[col = r][32 quad + 8 i + e]
+};
+
+constexpr float kWideLag = 8.0f;  // the reference maximum moves only when exceeded by 2^8
+
+template <int HPW>
+__device__ __forceinline__ void load_wide(wide_tile& t, const char* base, int64_t plane_bytes,
+                                          const wide_lane& wl, int stride_bytes)
+{
+    constexpr int TG = 16 / HPW, TPI = 4 / HPW;
+    const uint32_t koff = (uint32_t)(wl.ktok * stride_bytes + wl.kcol);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t.k[u] = ld16(base, koff + (uint32_t)(u * TPI * stride_bytes));
+    const char* vb = base + plane_bytes;
+    const uint32_t voff = (uint32_t)(wl.vtok * stride_bytes + wl.vcol);
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t.v[gi][j] = ld16(vb, voff + (uint32_t)((gi * TG + j) * stride_bytes));
+}
+
+// Last, partial tile of a pair: rows past the last valid token (index `last` in the tile) are
+// replaced by that token's row (finite data; their scores are masked).
+template <int HPW>
+__device__ __forceinline__ void load_wide_tail(wide_tile& t, const char* base, int64_t plane_bytes,
+                                               const wide_lane& wl, int stride_bytes, int last)
+{
+    constexpr int TG = 16 / HPW, TPI = 4 / HPW;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        t.k[u] = ld16(base, (uint32_t)(min(u * TPI + wl.ktok, last) * stride_bytes + wl.kcol));
+    const char* vb = base + plane_bytes;
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            t.v[gi][j] = ld16(vb, (uint32_t)(min(gi * TG + wl.vtok + j, last) * stride_bytes + wl.vcol));
+}
+
+template <int HPW, bool TAIL>
+__device__ __forceinline__ void compute_wide(const wide_tile& t, const bf16x8 (&qb)[4], wide_state& st,
+                                             float scale_log2e, int last, const wide_lane& wl,
+                                             kv_u32x4* kstage)
+{
+    constexpr int TG = 16 / HPW;
+    const int r = wl.r, quad = wl.quad;
+    // K rows -> staging buffer (row = token * HPW + head = 4 u + quad, pieces XOR-swizzled as in
+    // the one-head kernel) -> A operands
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int row = 4 * u + quad;
+        kstage[row * 16 + (r ^ (row & 15))] = t.k[u];
+    }
+    __builtin_amdgcn_wave_barrier();
+    f32x4 sacc[2];
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+        sacc[gi] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const kv_u32x4 ka = kstage[(16 * gi + wl.krow) * 16 + ((4 * kk + quad) ^ wl.krow)];
+            sacc[gi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka), qb[kk], sacc[gi], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+        float sv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            bool ok = wl.mine;
+            if (TAIL) ok = ok && (gi * TG + wl.vtok + i <= last);
+            sv[i] = ok ? sacc[gi][i] * scale_log2e : kNegInf;
+        }
+        float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        if (HPW == 2) mx = fmaxf(mx, __shfl_xor(mx, 16));
+        if (__builtin_amdgcn_ballot_w64(mx > st.m + kWideLag) != 0) {
+            const float m_new = (mx > st.m + kWideLag) ? mx : st.m;
+            const float alpha = fast_exp2(st.m - m_new);  // 1 where unchanged, 0 on first use
+            st.m = m_new;
+            st.l *= alpha;
+            const float col_alpha = __shfl(alpha, wl.src);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.o[e] *= col_alpha;
+        }
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(sv[i] - st.m);
+        st.l += (p[0] + p[1]) + (p[2] + p[3]);
+        const bf16x4_bits pb =
+            __builtin_bit_cast(bf16x4_bits, uint2{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3])});
+        // V^T operands: element e of the four loaded pieces, token pairs packed per dword
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int w = e >> 1;
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            const uint32_t lo = __builtin_amdgcn_perm(t.v[gi][1][w], t.v[gi][0][w], sel);
+            const uint32_t hi = __builtin_amdgcn_perm(t.v[gi][3][w], t.v[gi][2][w], sel);
+            const bf16x4_bits av = __builtin_bit_cast(bf16x4_bits, uint2{lo, hi});
+            st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, pb, st.o[e], 0, 0, 0);
+        }
+    }
+}
+
+template <int HPW, bool MIXED>
+__global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_args a)
+{
+    constexpr int TG = 16 / HPW, TSHIFT = HPW == 4 ? 3 : 4, TILE = 1 << TSHIFT;
+    __shared__ kv_u32x4 s_kstage[kSkWaves * 512];
+    __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
+    __shared__ int32_t s_ctx[kMaxBatch];
+    __shared__ int32_t s_wsum[kSkWaves];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const kv_view_dev& v = a.v;
+    const int P = a.pairs, C = a.cols, G = a.group;
+
+    split_pos sp;
+    if (!split_prologue<TSHIFT>(a, P, s_prefix, s_ctx, s_wsum, sp)) return;
+    int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hg = sp.pair, tile = sp.tile;
+    const int x1 = sp.x1, w = sp.w;
+
+    wide_lane wl;
+    wl.r = lane & 15;
+    wl.quad = lane >> 4;
+    wl.ktok = lane / (16 * HPW);
+    wl.kcol = (lane % (16 * HPW)) * 16;
+    wl.vtok = HPW == 4 ? 0 : 4 * (wl.quad & 1);
+    wl.vcol = HPW == 4 ? lane * 16 : (wl.quad >> 1) * 256 + wl.r * 16;
+    wl.krow = (wl.r % TG) * HPW + wl.r / TG;
+    {
+        const int b = wl.r / G;                            // head of this lane's column
+        const int head = HPW == 4 ? wl.quad : wl.quad >> 1;  // head of this lane's rows of S^T
+        wl.mine = (wl.r < C) && (head == b);
+        wl.src = (wl.r < C) ? (HPW == 4 ? b : 2 * b) * 16 + wl.r : lane;
+    }
+    const int64_t plane_bytes = v.plane_elems * 2;
+    // layout of the current sequence's blocks (MIXED: looked up per sequence; else the view's own)
+    kv_layout_dev lay = {v.block_tokens, v.block_shift, v.token_stride, v.head_off};
+    int stride_bytes, tiles_per_block, tile_blk_shift;
+    auto use_layout = [&]() {
+        stride_bytes = lay.token_stride * 2;
+        tiles_per_block = lay.block_tokens >> TSHIFT;  // capacity is a multiple of 16
+        tile_blk_shift = lay.block_shift >= TSHIFT ? lay.block_shift - TSHIFT : -1;
+    };
+    use_layout();
+    kv_u32x4* kstage = s_kstage + wave * 512;
+
+    while (x0 < x1) {
+        if (MIXED) {
+            const int vid = min(max(uniform(a.view_ids[s]), 0), a.n_views - 1);
+            lay = a.lay[vid];
+            use_layout();
+        }
+        const int n = uniform(s_ctx[s]);
+        const int seg_end = min(tiles_s, tile + (x1 - x0));
+        const int n_full = n >> TSHIFT;            // tiles of this pair with every token valid
+        const int full_end = min(seg_end, n_full);
+        const int32_t* trow = a.table + (int64_t)s * a.table_stride;
+        const char* head_base = reinterpret_cast<const char*>(a.pool + lay.head_off + hg * (HPW * D));
+        const int last_block = (n - 1) / lay.block_tokens;
+
+        bf16x8 qb[4];
+        {
+            const char* qrows = reinterpret_cast<const char*>(a.q + ((int64_t)s * v.n_q_local + hg * C) * D);
+            const uint32_t qoff = (uint32_t)(min(wl.r, C - 1) * (D * 2) + wl.quad * 16);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                kv_u32x4 raw = ld16_cached(qrows, qoff + kk * 64);
+                if (wl.r >= C) raw = kv_u32x4{0u, 0u, 0u, 0u};
+                qb[kk] = as_bf16x8(raw);
+            }
+        }
+        wide_state st;
+        st.m = wl.mine ? kNegInf : 0.f;
+        st.l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // block ids of 64 consecutive blocks, one per lane, refilled when the walk leaves them
+        auto tile_block = [&](int i) -> int {
+            return tile_blk_shift >= 0 ? (i >> tile_blk_shift) : i / tiles_per_block;
+        };
+        int id_base = tile_block(tile);
+        int idv = trow[min(id_base + lane, last_block)];
+        auto tile_base = [&](int i) -> const char* {
+            const int jb = tile_block(i);
+            if (jb - id_base >= 64) {
+                id_base = jb;
+                idv = trow[min(id_base + lane, last_block)];
+            }
+            const int blk = __builtin_amdgcn_readlane(idv, jb - id_base);
+            const int slot0 = (i - jb * tiles_per_block) << TSHIFT;
+            return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot0 * stride_bytes;
+        };
+
+        wide_tile ta, tb;
+        int i = tile;
+        if (i < full_end) load_wide<HPW>(ta, tile_base(i), plane_bytes, wl, stride_bytes);
+        while (i + 2 <= full_end) {
+            load_wide<HPW>(tb, tile_base(i + 1), plane_bytes, wl, stride_bytes);
+            compute_wide<HPW, false>(ta, qb, st, a.scale_log2e, TILE - 1, wl, kstage);
+            if (i + 2 < full_end) load_wide<HPW>(ta, tile_base(i + 2), plane_bytes, wl, stride_bytes);
+            compute_wide<HPW, false>(tb, qb, st, a.scale_log2e, TILE - 1, wl, kstage);
+            i += 2;
+        }
+        if (i < full_end) {
+            compute_wide<HPW, false>(ta, qb, st, a.scale_log2e, TILE - 1, wl, kstage);
+            ++i;
+        }
+        if (seg_end > full_end) {
+            // the pair's last tile, partly filled: tokens TILE * n_full .. n - 1
+            const int last = n - 1 - TILE * n_full;  // 0 .. TILE - 2
+            load_wide_tail<HPW>(ta, tile_base(n_full), plane_bytes, wl, stride_bytes, last);
+            compute_wide<HPW, true>(ta, qb, st, a.scale_log2e, last, wl, kstage);
+        }
+
+        // ---- piece done: final rows or partial ------------------------------------------------------
+        st.l += __shfl_xor(st.l, 16);
+        st.l += __shfl_xor(st.l, 32);
+        const float m_col = __shfl(st.m, wl.src);
+        const bool whole = (tile == 0 && seg_end == tiles_s);
+        if (wl.r < C) {
+            if (whole) {
+                const float inv = 1.0f / st.l;
+                uint16_t* dst = a.out + ((int64_t)s * v.n_q_local + hg * C + wl.r) * D + 32 * wl.quad;
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) {
+                    kv_u32x4 pk;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        pk[u] = pack_bf16x2(st.o[2 * u][ii] * inv, st.o[2 * u + 1][ii] * inv);
+                    *reinterpret_cast<kv_u32x4*>(dst + 8 * ii) = pk;
+                }
+            } else {
+                const int64_t slot = (int64_t)w + (int64_t)s * P + hg;
+                float* dst = a.part_acc + (slot * C + wl.r) * D + 32 * wl.quad;
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) {
+                    *reinterpret_cast<f32x4*>(dst + 8 * ii) =
+                        f32x4{st.o[0][ii], st.o[1][ii], st.o[2][ii], st.o[3][ii]};
+                    *reinterpret_cast<f32x4*>(dst + 8 * ii + 4) =
+                        f32x4{st.o[4][ii], st.o[5][ii], st.o[6][ii], st.o[7][ii]};
+                }
+                if (wl.quad == 0) {
+                    a.part_ml[(slot * C + wl.r) * 2 + 0] = m_col;
+                    a.part_ml[(slot * C + wl.r) * 2 + 1] = st.l;
+                }
+            }
+        }
+
+        // ---- next pair ------------------------------------------------------------------------------
+        x0 += seg_end - tile;
+        tile = 0;
+        if (++hg == P) {
+            hg = 0;
+            do {
+                ++s;
+                tiles_s = (s < a.batch) ? uniform(s_prefix[s + 1]) - uniform(s_prefix[s]) : 1;
+            } while (tiles_s == 0);
+        }
+    }
+}
+
 // Merge the pieces of one (sequence, local query head), or write zeros for an empty context.
 // The 256 lanes of a workgroup are column groups of 4 elements x slices of the piece list.  A
 // short list (the common case: a pair cut over a few wavefronts) is merged by one workgroup as
@@ -443,8 +759,8 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
 {
     const int qi = blockIdx.x, s = blockIdx.y, z = blockIdx.z, tid = threadIdx.x;
     const kv_view_dev& v = a.v;
-    const int Hl = v.n_kv_local, G = a.group;
-    __shared__ float s_max[4];
+    const int Hl = a.pairs, G = a.cols;  // pairs per sequence, output rows per pair
+    __shared__ float s_max[32];
     __shared__ float s_acc[8 * D];
     __shared__ float s_l[32];
     // tiles before sequence s and in total, as computed by the main kernel
@@ -457,7 +773,7 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
         if (z == 0 && tid < D) dst[tid] = 0;
         return;
     }
-    const int tiles_s = (n + 31) >> 5;
+    const int tiles_s = (n + (1 << a.tile_shift) - 1) >> a.tile_shift;
     const int hl = qi / G, g = qi - hl * G;
     const int total = all * Hl;
     const int tpw = (total + a.n_waves - 1) / a.n_waves;
@@ -472,25 +788,27 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     const int col0 = wide ? z * cols : 0;
     const int cg = tid % ncg, slice = tid / ncg;
 
-    float mm = kNegInf;
-    for (int w = w_first + tid; w <= w_last; w += 256) mm = fmaxf(mm, a.part_ml[((w + pair) * G + g) * 2]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off));
-    if ((tid & 63) == 0) s_max[tid >> 6] = mm;
-    __syncthreads();
-    mm = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-
-    float ll = 0.f;
+    // one pass over the pieces of this slice, rescaling on the fly; the slices are then brought
+    // to the common maximum and summed through LDS
+    float mr = kNegInf, ll = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int w = w_first + slice; w <= w_last; w += nsl) {
         const int64_t rec = (w + pair) * G + g;
         const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
-        const float cw = fast_exp2(ml.x - mm);
-        ll += ml.y * cw;
-        acc += *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4) * cw;
+        const f32x4 part = *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4);
+        const float mn = fmaxf(mr, ml.x);          // finite: every piece holds a valid token
+        const float c_old = fast_exp2(mr - mn), c_new = fast_exp2(ml.x - mn);
+        ll = ll * c_old + ml.y * c_new;
+        acc = acc * c_old + part * c_new;
+        mr = mn;
     }
-    *reinterpret_cast<f32x4*>(&s_acc[slice * cols + cg * 4]) = acc;
-    if (cg == 0) s_l[slice] = ll;
+    if (cg == 0) s_max[slice] = mr;
+    __syncthreads();
+    float mm = kNegInf;
+    for (int k = 0; k < nsl; ++k) mm = fmaxf(mm, s_max[k]);
+    const float cs = fast_exp2(mr - mm);           // 0 for a slice without pieces
+    *reinterpret_cast<f32x4*>(&s_acc[slice * cols + cg * 4]) = acc * cs;
+    if (cg == 0) s_l[slice] = ll * cs;
     __syncthreads();
     if (tid < cols) {
         float tot = 0.f, lt = 0.f;
@@ -504,26 +822,64 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
 
 }  // namespace
 
+// Adjacent KV heads one wavefront takes (1: the one-head kernel).  With HPW heads the HPW * G
+// query rows of a pair must fit the 16 columns of the matrix-core tile.
+static int wide_heads(const kv_view* view)
+{
+    if (kv_option_variant() & 4) return 1;
+    // measured: a gain of 2-5 % where the token rows hold more heads than one wavefront takes or
+    // the query rows fill the 16 columns; a small loss for two heads of a two-head row otherwise
+    const int G = view->group, Hl = view->n_kv_local;
+    if (G <= 4 && Hl % 4 == 0) return 4;
+    if (G > 4 && G <= 8 && Hl % 2 == 0 && Hl >= 4) return 2;
+    return 1;
+}
+
+// Partial results: one slot per (wavefront, pair) piece, n_waves + batch * pairs at most, each
+// with `cols` rows of (acc[128], m, l).  Sized for the larger of the two kernels' needs so that the
+// figure does not depend on the variant option.
+static void workspace_layout(const kv_view* view, int batch, int n_waves, int hpw, size_t& acc, size_t& ml)
+{
+    const size_t pairs = (size_t)view->n_kv_local / hpw, cols = (size_t)view->group * hpw;
+    const size_t slots = (size_t)n_waves + (size_t)batch * pairs;
+    acc = (slots * cols * D * 4 + 255) / 256 * 256;
+    ml = (slots * cols * 2 * 4 + 255) / 256 * 256;
+}
+
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves)
 {
-    const size_t slots = (size_t)n_waves + (size_t)batch * view->n_kv_local;
-    const size_t acc = (slots * view->group * D * 4 + 255) / 256 * 256;
-    const size_t ml = (slots * view->group * 2 * 4 + 255) / 256 * 256;
+    size_t need = 0;
+    for (int hpw = 1; hpw <= 4; hpw *= 2) {
+        if (view->n_kv_local % hpw != 0 || view->group * hpw > 16) continue;
+        size_t acc, ml;
+        workspace_layout(view, batch, n_waves, hpw, acc, ml);
+        if (acc + ml > need) need = acc + ml;
+    }
     const size_t prefix = ((size_t)(batch + 1) * 4 + 255) / 256 * 256;
-    return acc + ml + prefix;
+    return need + prefix;
 }
 
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st)
 {
-    const size_t slots = (size_t)a.n_waves + (size_t)a.batch * view->n_kv_local;
-    const size_t acc = (slots * view->group * D * 4 + 255) / 256 * 256;
+    const int hpw = wide_heads(view);
+    a.heads_per_wave = hpw;
+    a.pairs = view->n_kv_local / hpw;
+    a.cols = view->group * hpw;
+    a.tile_shift = hpw == 4 ? 3 : hpw == 2 ? 4 : 5;
+    size_t acc, ml;
+    workspace_layout(view, a.batch, a.n_waves, hpw, acc, ml);
     a.part_acc = (float*)workspace;
-    const size_t ml = (slots * view->group * 2 * 4 + 255) / 256 * 256;
     a.part_ml = (float*)((char*)workspace + acc);
     a.prefix_out = (int32_t*)((char*)workspace + acc + ml);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
-    if (a.view_ids) {
+    if (hpw == 4) {
+        if (a.view_ids) hipLaunchKernelGGL((decode_wide_kernel<4, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((decode_wide_kernel<4, false>), grid, block, 0, st, a);
+    } else if (hpw == 2) {
+        if (a.view_ids) hipLaunchKernelGGL((decode_wide_kernel<2, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((decode_wide_kernel<2, false>), grid, block, 0, st, a);
+    } else if (a.view_ids) {
         hipLaunchKernelGGL((decode_streamk_kernel<1, 1, true>), grid, block, 0, st, a);
     } else
     switch (kv_option_variant() & 3) {
@@ -536,8 +892,8 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     int rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn launch");
     if (rc) return rc;
     slot = kv_prof_begin(KV_PROF_DECODE_MERGE, st);
-    // eight or more pieces per pair on average: expect long lists, split their columns
-    const bool few_pairs = (int64_t)a.batch * view->n_kv_local * 8 <= a.n_waves;
+    // kMergeLong or more pieces per pair on average: expect long lists, split their columns
+    const bool few_pairs = (int64_t)a.batch * a.pairs * kMergeLong <= a.n_waves;
     hipLaunchKernelGGL(decode_streamk_merge_kernel,
                        dim3((unsigned)view->n_q_local, (unsigned)a.batch, few_pairs ? (unsigned)kMergeSplit : 1u),
                        dim3(256), 0, st, a);

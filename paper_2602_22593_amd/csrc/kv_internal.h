@@ -114,6 +114,12 @@ struct kv_streamk_args {
     const int32_t* view_ids;  // [batch] index into lay[] per sequence, or null: every sequence under v
     int32_t n_views;
     kv_layout_dev lay[KV_MAX_MIXED_VIEWS];
+    // unit of the split, filled in by kv_streamk_launch: a pair is (sequence, `heads_per_wave`
+    // adjacent local KV heads), a tile 2^tile_shift tokens of a pair
+    int32_t heads_per_wave;  // 1, 2 or 4
+    int32_t pairs;           // pairs per sequence = n_kv_local / heads_per_wave
+    int32_t cols;            // output rows per pair = heads_per_wave * group (<= 16)
+    int32_t tile_shift;      // 5 (one head), 4 (two heads) or 3 (four heads)
 };
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

@@ -540,8 +540,8 @@ static int launch_streamk(const void* q, void* out, const void* kv_pool, const i
                           size_t workspace_bytes, hipStream_t st, const int32_t* view_ids,
                           const kv_view* const* views, int n_views)
 {
-    // tiles of 32 tokens over all (sequence, head) pairs must fit 31 bits
-    if (((int64_t)max_ctx_len / 32 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
+    // tiles (of 8 tokens at the least) over all (sequence, head) pairs must fit 31 bits
+    if (((int64_t)max_ctx_len / 8 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
         return KV_ERR_UNSUPPORTED;
     const int n_waves = streamk_waves();
     const size_t need_sk = kv_streamk_workspace_bytes(view, batch, n_waves);

@@ -93,12 +93,13 @@ def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk, kernel):
         assert np.array_equal(got[0, i], bf16_bits_to_f64(c.V[c.seq_off[0], g]))
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("wpc", [4, 12])
 def test_even_split_kernel_variants(variant, wpc):
-    """The even-split matrix-core kernel in its build variants (K fetched operand-wise or row-wise
-    through LDS; with or without register double buffering) and launch widths; lengths chosen so
-    that wavefront ranges cross sequence and head boundaries and single-piece pairs occur."""
+    """The even-split matrix-core kernel in its build variants (several adjacent KV heads per
+    wavefront where the shape allows, or always one: bit 2; for one head, K fetched operand-wise or
+    row-wise through LDS, with or without register double buffering) and launch widths; lengths
+    chosen so that wavefront ranges cross sequence and head boundaries and single-piece pairs occur."""
     kv.kv_set_option("variant", variant)
     kv.kv_set_option("waves_per_cu", wpc)
     try:
@@ -114,6 +115,51 @@ def test_even_split_kernel_variants(variant, wpc):
     finally:
         kv.kv_set_option("variant", 0)
         kv.kv_set_option("waves_per_cu", 0)
+
+
+@pytest.mark.parametrize("hq,hkv,triple", [
+    (32, 8, (LAYOUT_DP, 1, 0)),    # G 4: four heads per wavefront, two head groups per sequence
+    (32, 8, (LAYOUT_TP, 2, 1)),    # G 4: the rank's four heads are one group (contiguous 1 KiB rows)
+    (32, 8, (LAYOUT_DP, 2, 1)),    # the same heads read in place from DP-layout blocks
+    (64, 8, (LAYOUT_DP, 1, 0)),    # G 8: two heads per wavefront
+    (64, 8, (LAYOUT_TP, 2, 0)),
+    (24, 8, (LAYOUT_DP, 1, 0)),    # G 3: 12 of the 16 columns in use
+    (16, 8, (LAYOUT_TP, 2, 1)),    # G 2
+    (8, 8, (LAYOUT_DP, 1, 0)),     # G 1
+])
+def test_several_heads_per_wavefront_every_tail_length(hq, hkv, triple):
+    """The kernel that gives a wavefront 2 or 4 adjacent KV heads: every context length from 0 to
+    40 (every fill of the last 8- or 16-token tile, with and without full tiles before it), plus
+    lengths around block and window boundaries; the pool is NaN-poisoned outside the valid tokens.
+    Same shapes with one head per wavefront (variant bit 2) as the cross-check of the option."""
+    lens = np.array(list(range(41)) + [127, 128, 129, 1023, 1025, 2050], dtype=np.int32)
+    w = wl.Workload("wide", 80 + hq // 8, hq, hkv, 128, 16, len(lens), "x", ())
+    c = make_case(w, triple, lens)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    try:
+        for variant in (0, 4):
+            kv.kv_set_option("variant", variant)
+            got = run_gpu_decode(c, gpu_view(w, triple))
+            check_close(got, want, f"{hq}/{hkv} {triple} variant {variant}")
+            assert (got[0] == 0).all()
+            G = hq // hkv
+            for i in range(c.info["n_q_local"]):     # ctx_len 1 -> the V row itself
+                g = c.info["kv_head0"] + i // G
+                assert np.array_equal(got[1, i], bf16_bits_to_f64(c.V[c.seq_off[1], g]))
+    finally:
+        kv.kv_set_option("variant", 0)
+
+
+def test_long_sequences_cut_over_every_wavefront_head_groups():
+    """DP view, four heads per wavefront: two head groups of one long sequence cut over all
+    wavefronts (hundreds of pieces per pair, the merge kernel's long-list grid), next to a short
+    sequence whose pairs are single pieces."""
+    w = wl.Workload("long4", 73, 32, 8, 128, 16, 3, "x", ())
+    ctx = np.array([9, 30011, 200], dtype=np.int32)
+    c = make_case(w, (LAYOUT_DP, 1, 0), ctx)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    got = run_gpu_decode(c, gpu_view(w, (LAYOUT_DP, 1, 0)))
+    check_close(got, want, "long sequence, head groups")
 
 
 def test_one_long_sequence_cut_over_every_wavefront():

@@ -114,11 +114,13 @@ def test_tp_ranks_reproduce_the_dp_engine():
         total = np.zeros((len(ctx), HIDDEN))
         for r in range(m):
             _, attn_r, y_r = run_rank(w, (LAYOUT_TP, m, r), m, r, x, wqkv, wo, ctx, K_old, V_old)
-            # a rank's attention output is the DP engine's for the heads it owns (the same numbers up to
-            # the order in which the pieces of a sequence are merged: one bf16 ulp at most)
+            # a rank's attention output is the DP engine's for the heads it owns, up to what the kernels
+            # serving the two views do differently (heads per wavefront, where a sequence is cut, the
+            # reference maximum the bf16 probabilities are scaled by): a few bf16 ulps at most
             hql = HQ // m
             a_r, a_dp = bf16_bits_to_f64(attn_r), bf16_bits_to_f64(attn_dp[:, r * hql:(r + 1) * hql])
-            assert (np.abs(a_r - a_dp) <= np.abs(a_dp) * 2.0 ** -7 + 1e-4).all(), (m, r)
+            # (bf16 probabilities: 2^-9 relative per term of a sum of O(1) values, plus the output rounding)
+            assert (np.abs(a_r - a_dp) <= np.abs(a_dp) * 2.0 ** -6 + 4e-3).all(), (m, r, float(np.abs(a_r - a_dp).max()))
             total += bf16_bits_to_f64(y_r)
         # sum of the ranks' bf16 partials vs the DP engine's single bf16 result: m + 1 roundings apart
         want = bf16_bits_to_f64(y_dp)
