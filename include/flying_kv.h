@@ -292,6 +292,9 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
  *                   instead of through LDS, bit 1 no register double buffering (both for the
  *                   one-head-per-wavefront kernel), bit 2 one KV head per wavefront even where
  *                   several adjacent heads per wavefront are possible
+ *   "linear_splits" workgroups sharing the input dimension of one output tile in kv_linear_view
+ *                   (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
+ *                   follows the option, so size the workspace after setting it
  * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
 int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);

@@ -83,6 +83,7 @@ int64_t kv_option_chunk_tokens();
 int64_t kv_option_force_kernel();
 int64_t kv_option_waves_per_cu();
 int64_t kv_option_variant();
+int64_t kv_option_linear_splits();
 
 // Per-kernel event brackets for kv_profile_*: begin returns a slot (or -1 when disabled).
 int kv_prof_begin(int which, hipStream_t st);

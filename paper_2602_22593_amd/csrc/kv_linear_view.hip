@@ -8,17 +8,19 @@
 // Shaped for decode batches (M up to a few hundred rows): the weight slice is streamed from HBM
 // once per 64 batch rows and is the dominant traffic; x is small, but every weight row needs all
 // of it, so it must be shared: a workgroup of four wavefronts owns 64 logical weight rows (16 per
-// wavefront) x 64 batch rows and walks its part of the input dimension in steps of 128.  Per
-// step the workgroup stages the x slab (64 rows x 128) in LDS once, laid out in MFMA operand
-// order so that each B operand is one contiguous kilobyte, and every wavefront accumulates
+// wavefront) x 64 batch rows and walks its part of the input dimension in slabs of 128.  The x
+// slab (64 rows x 128) is staged in LDS once per workgroup, laid out in MFMA operand order so
+// that each B operand is one contiguous kilobyte, and every wavefront accumulates
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
-// with 16x16x32 bf16 MFMA, taking its A operand (16 weight rows) straight from global memory in
-// operand order.  The next step's W and x pieces are in flight while the current one is
-// consumed; LDS is double buffered, one barrier per step.
-// A decode batch gives few such workgroups for 256 compute units, and a wavefront streams at the
-// pace memory latency allows, so the input dimension is cut over `splits` workgroups (grid.z):
-// each then leaves an fp32 partial tile in the workspace and a second, small kernel adds the
-// splits in a fixed order and rounds to bf16 (deterministic; no atomics).
+// with 16x16x32 bf16 MFMA.  Its 16 weight rows are fetched as they lie in memory (a load
+// instruction covers four rows x 256 contiguous bytes) and pass through a wavefront-private,
+// XOR-swizzled LDS buffer into the A-operand arrangement.
+// The walk is paced by memory latency, not bandwidth (per-workgroup timestamps: one round trip
+// under this load is 4-5 us), so the loads of four slabs (a chunk: 64 KiB of W and 64 KiB of x
+// per workgroup) are all issued before anything waits, and the input dimension is cut over
+// `splits` workgroups (grid.z) so that a workgroup has about two chunks: each then leaves an fp32
+// partial tile in the workspace and a second, small kernel adds the splits in a fixed order and
+// rounds to bf16 (deterministic; no atomics).
 #include <string.h>
 
 #include "decode_common.h"
@@ -30,7 +32,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kTileRows = 64;   // logical weight rows per workgroup: 16 per wavefront
 constexpr int kColBlocks = 4;   // 16-row blocks of x per workgroup
-constexpr int kSlab = 128;      // input features per step
+constexpr int kSlab = 128;      // input features per slab
+constexpr int kChunk = 4;       // slabs whose loads a workgroup issues together
 
 struct linear_args {
     const uint16_t* x;
@@ -48,12 +51,14 @@ struct linear_args {
     float* part;            // [splits][M][Nl] fp32 when splits > 1
 };
 
-__global__ __launch_bounds__(kThreads, 3) void linear_view_kernel(linear_args p)
+__global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
 {
-    // x slab in operand order: piece (kk, cb, quad, c) = x[16 cb + c][32 kk + 8 quad .. + 8) of the
-    // step sits at ((kk * 4 + cb) * 4 + quad) * 16 + (c ^ (4 kk + quad)): a B operand is one
+    // x slabs of one chunk in operand order: piece (kk, cb, quad, c) = x[16 cb + c][32 kk + 8 quad .. + 8)
+    // of a slab sits at ((kk * 4 + cb) * 4 + quad) * 16 + (c ^ (4 kk + quad)): a B operand is one
     // contiguous kilobyte, and the XOR spreads the row-wise staging writes over all banks
-    __shared__ kv_u32x4 s_x[2][4 * kColBlocks * 64];
+    __shared__ kv_u32x4 s_x[kChunk][4 * kColBlocks * 64];
+    // weight rows of one slab, per wavefront: piece c (16 bytes) of row t at t * 16 + (c ^ t)
+    __shared__ kv_u32x4 s_w[kThreads / 64][256];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -65,9 +70,12 @@ __global__ __launch_bounds__(kThreads, 3) void linear_view_kernel(linear_args p)
     int seg = 0;
     while (seg + 1 < p.n_seg && n0 >= p.seg_first[seg + 1]) ++seg;
     const int64_t phys0 = p.seg_start[seg] + (n0 - p.seg_first[seg]);
-    const char* wbase = reinterpret_cast<const char*>(p.w + (phys0 + 16 * wave + r) * p.ldw + p.col_start) + quad * 16;
+    // load instruction u of a slab: row 4 u + quad of the wavefront's 16, piece r of its 16
+    const char* wbase = reinterpret_cast<const char*>(p.w + (phys0 + 16 * wave + quad) * p.ldw + p.col_start) + r * 16;
+    const int64_t w_step4 = 4 * p.ldw * 2;   // bytes between rows 4 apart
+    kv_u32x4* const sw = s_w[wave];
 
-    // staging: thread t moves pieces t, t + 256, t + 512, t + 768 of the slab; piece id = 16 row + q,
+    // staging: thread t moves pieces t, t + 256, t + 512, t + 768 of a slab; piece id = 16 row + q,
     // q = 4 kk + quad the 16-byte piece within the row's 128 elements (rows past M repeat the last)
     const char* xsrc[4];
     int xdst[4];
@@ -78,7 +86,7 @@ __global__ __launch_bounds__(kThreads, 3) void linear_view_kernel(linear_args p)
         xdst[i] = (((q >> 2) * kColBlocks + (row >> 4)) * 4 + (q & 3)) * 16 + ((row & 15) ^ q);
     }
 
-    // this workgroup's steps: [step, last)
+    // this workgroup's slabs: [step, last)
     const int total = p.Kl / kSlab;
     const int per_split = (total + p.splits - 1) / p.splits;
     int step = (int)blockIdx.z * per_split;
@@ -88,73 +96,58 @@ __global__ __launch_bounds__(kThreads, 3) void linear_view_kernel(linear_args p)
 #pragma unroll
     for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Step k travels in register stage k % 2: its loads are issued during step k - 2 (as soon as
-    // that step's arithmetic has released the stage), its x pieces are written to LDS buffer k % 2
-    // at the end of step k - 1, its weights are used from the registers in step k.  The
-    // steady-state loop refills a stage in every step with unconditional loads (every wait then
-    // leaves exactly the younger stage in flight); the last two steps run without loads.
-    kv_u32x4 a_st[2][4], x_st[2][4];
-    auto fetch = [&](int stg, int st) {
-        const int64_t off = (int64_t)st * (kSlab * 2);
+    // A chunk is up to kChunk slabs.  All of a chunk's loads (weights first, then x) are issued
+    // before anything waits: the walk along the input dimension is paced by memory latency, so a
+    // workgroup should need as few round trips as it can, and the splits are chosen to give it one
+    // or two chunks.
+    kv_u32x4 a_st[kChunk][4], x_st[kChunk][4];
+    auto compute = [&](int j) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            a_st[stg][kk] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(wbase + off + kk * 64));
+        for (int u = 0; u < 4; ++u) {
+            const int row = 4 * u + quad;
+            sw[row * 16 + (r ^ row)] = a_st[j][u];
+        }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x_st[stg][i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off);
-    };
-    auto stash = [&](int stg) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) s_x[stg][xdst[i]] = x_st[stg][i];
-    };
-    auto compute = [&](int stg) {
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
+        for (int kk = 0; kk < 4; ++kk) {
+            const kv_u32x4 a = sw[r * 16 + ((4 * kk + quad) ^ r)];
 #pragma unroll
             for (int cb = 0; cb < kColBlocks; ++cb) {
-                const kv_u32x4 b = s_x[stg][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_st[stg][kk]), as_bf16x8(b), acc[cb], 0, 0, 0);
+                const kv_u32x4 b = s_x[j][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), acc[cb], 0, 0, 0);
             }
+        }
+        __builtin_amdgcn_wave_barrier();
     };
-
-    if (step < last) {
-        fetch(0, step);
-        fetch(1, min(step + 1, last - 1));
-        stash(0);
+    for (bool first = true; step < last; step += kChunk, first = false) {
+        const int n_slabs = min(kChunk, last - step);
+        const int64_t off = (int64_t)step * (kSlab * 2);
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < n_slabs) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    a_st[j][u] = __builtin_nontemporal_load(
+                        reinterpret_cast<const kv_u32x4*>(wbase + off + j * (kSlab * 2) + u * w_step4));
+            }
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < n_slabs) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    x_st[j][i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off + j * (kSlab * 2));
+            }
+        if (!first) __syncthreads();   // the previous chunk's operands have been read
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < n_slabs) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_x[j][xdst[i]] = x_st[j][i];
+            }
         __syncthreads();
-        int cur = 0;
-        for (;;) {
-            if (step + 2 >= last) break;
-            compute(0);
-            fetch(0, step + 2);
-            stash(1);
-            __syncthreads();
-            ++step;
-            if (step + 2 >= last) {
-                cur = 1;
-                break;
-            }
-            compute(1);
-            fetch(1, step + 2);
-            stash(0);
-            __syncthreads();
-            ++step;
-        }
-        // steps `step` (in stage cur, already in LDS) and possibly `step + 1` (other stage) remain
-        if (cur == 0) {
-            compute(0);
-            if (step + 1 < last) {
-                stash(1);
-                __syncthreads();
-                compute(1);
-            }
-        } else {
-            compute(1);
-            if (step + 1 < last) {
-                stash(0);
-                __syncthreads();
-                compute(0);
-            }
-        }
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+            if (j < n_slabs) compute(j);
     }
 
     // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 wave + 4 quad + i]
@@ -190,16 +183,21 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
     *reinterpret_cast<uint2*>(p.y + m * p.ldy + n) = pk;
 }
 
-// Workgroups sharing the input dimension of one output tile: enough for about two workgroups
-// per compute unit in total (measured best for the Llama-8B projections: more splits only add
-// partial traffic), at least two steps each, at most 16.
-int pick_splits(int64_t tiles, int total_steps)
+// Workgroups sharing the input dimension of one output tile.  Measured on the Llama-8B
+// projections (batch 16..256, TP 1..8): the optimum is flat around two chunks per workgroup; more
+// splits shorten the chain of memory round trips but their partial tiles cost as much again, fewer
+// leave compute units idle.  So: two chunks each, more splits only while the launch would have
+// fewer than 192 workgroups, fewer when it would have more than 1024; at most 16.
+int pick_splits(int64_t tiles, int total_slabs)
 {
-    int s = (int)((512 + tiles - 1) / tiles);
-    s = s < 1 ? 1 : s;
+    int s = (total_slabs + 2 * kChunk - 1) / (2 * kChunk);
+    while (s < 16 && s < total_slabs && tiles * s < 192) ++s;
+    while (s > 1 && tiles * s > 1024) --s;
+    const int64_t forced = kv_option_linear_splits();
+    if (forced > 0) s = (int)forced;
     s = s > 16 ? 16 : s;
-    const int most = total_steps / 2 > 0 ? total_steps / 2 : 1;
-    return s > most ? most : s;
+    s = s > total_slabs ? total_slabs : s;
+    return s < 1 ? 1 : s;
 }
 
 int64_t view_rows(const kv_weight_view* view)

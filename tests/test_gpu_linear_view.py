@@ -87,3 +87,23 @@ def test_output_rows_outside_the_batch_are_untouched():
     assert (out[M:] == 7.0).all() and (out[:, hidden:] == 7.0).all()
     check(out[:M, :hidden].contiguous().cpu().view(torch.int16).numpy().view(np.uint16),
           ow.linear_view(x, w, ow.weight_view(0, 0, 1, hidden, kin)), kin, "padded out")
+
+
+@pytest.mark.parametrize("splits", [0, 1, 2, 3, 5, 16])
+@pytest.mark.parametrize("slabs", [1, 4, 7, 9])
+def test_every_cut_of_the_input_dimension(slabs, splits):
+    """The input dimension in 128-wide slabs, four to a chunk: one slab, exactly one chunk, a chunk
+    and a part (7), two chunks and one slab (9); cut over 1, 2, 3, 5 and (capped at the slab count)
+    16 workgroups, and by the library's own choice (0).  A row-parallel view (column range) of a
+    wider stored weight, batch past one tile."""
+    K, M, N = 128 * slabs, 70, 192
+    x, w = bits((M, K), 60 + slabs), bits((N, 2 * K + 64), 70 + slabs)
+    ov = ow.WeightView(((0, N),), K + 64, K)
+    gv = gpu_view(ov)
+    kv.kv_set_option("linear_splits", splits)
+    try:
+        y = kv.kv_linear_view(dev(x), dev(w), gv)
+        torch.cuda.synchronize()
+    finally:
+        kv.kv_set_option("linear_splits", 0)
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), ow.linear_view(x, w, ov), K, f"slabs {slabs} splits {splits}")
