@@ -1,4 +1,7 @@
 // Matrix-core decode attention with an even split of the whole batch over resident wavefronts.
+// Two main kernels share the split, the workspace and the merge kernel: decode_streamk_kernel (one
+// KV head per wavefront, described first) and decode_wide_kernel (2 or 4 adjacent heads per
+// wavefront, described where it is defined); kv_streamk_launch picks one per view.
 //
 // The batch is flattened into tiles of 32 tokens of one (sequence, local KV head) pair, pairs
 // ordered (sequence, head) with the head fastest.  With T tiles in total and W wavefronts
