@@ -12,10 +12,14 @@
 // Per tile and row block, lane l = (c = l % 16, quad = l / 16), exactly as in the decode kernel:
 //   S^T[token][c] = K[token][:] . q[c][:]     A operand = K rows from LDS (token 16 h + 4 (r % 4)
 //                                             + r / 4 in A row r of half h), B operand = q
-//   O^T[e][c]     = sum_t V[t][e] P[c][t]     A operand = V^T, built in the lane from 16-byte
-//                                             pieces of V rows with byte permutes
-// so the accumulator layout of S^T is already the B layout of the second product and only the
-// running maximum crosses lanes.  Column c of row block b of wavefront w is row
+//   O^T[e][c]     = sum_t V[t][e] P[c][t]     A operand = V^T, read from the row-major V tile in
+//                                             LDS with the transposing 64-bit read: a lane hands
+//                                             in the address of four consecutive elements of one
+//                                             row and receives one element of each of four rows
+// so the accumulator layout of S^T is already the B layout of the second product and the running
+// maximum crosses lanes only when it moves.  The sum of the weights of a column comes out of the
+// matrix cores as well (one more product, with an all-ones A operand), from the same bf16 weights
+// as the numerator.  Column c of row block b of wavefront w is row
 // rho = (w R + b) 16 + c of the tile: token rho / Gp, head rho % Gp, Gp = G rounded up to a power
 // of two (rows with head >= G are padding).  The causal mask keeps
 // token t for a query at position pos iff t <= pos; since pos < ctx_len it also masks the slots
@@ -49,10 +53,23 @@ struct prefill_args {
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+typedef short bits16x4 __attribute__((ext_vector_type(4)));
+typedef short bits16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) bits16x4* lds_bits16x4_ptr;
+
+// Transposing LDS read.  Within each group of 16 lanes, lane i passes the address of four
+// consecutive 16-bit elements (a row); lane i receives, as element j, element i % 4 of the row
+// passed by lane 4 j + i / 4 of its group.
+__device__ __forceinline__ bits16x4 lds_read_transposed(const void* p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_bits16x4_ptr)p);
+}
+
 template <int R>
 __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefill_args a)
 {
-    // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)), V pieces plain
+    // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)); V pieces at
+    // c ^ (2 * ((t / 4) % 4)), which puts the four rows a transposing read touches in different banks
     __shared__ kv_u32x4 s_k[2][512];
     __shared__ kv_u32x4 s_v[2][512];
 
@@ -147,19 +164,27 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         for (int h = 0; h < 2; ++h) {
             const int row = 16 * h + ld_row;
             s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[stg][h];
-            s_v[buf][row * 16 + ld_c] = stage_v[stg][h];
+            s_v[buf][row * 16 + (ld_c ^ (2 * ((row >> 2) & 3)))] = stage_v[stg][h];
         }
     };
 
-    float m[R], l[R];
-    f32x4 o[R][8];  // o[b][j][i] = O[column][32 quad + 8 i + j]
+    float m[R];
+    f32x4 l[R];     // sum of the weights of the column, the same in all four entries and lanes of it
+    f32x4 o[R][8];  // o[b][j][i] = O[column][16 j + 4 quad + i]
 #pragma unroll
     for (int b = 0; b < R; ++b) {
         m[b] = kNegInf;
-        l[b] = 0.f;
+        l[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    // this lane's part of the V^T operand of output block j: elements [16 j + 4 (r % 4), + 4) of
+    // tokens 4 (r / 4) + quad (first read) and 16 + 4 (r / 4) + quad (second) of the tile; A row r
+    // then is element 16 j + r, contraction index 8 quad + 4 h + i is token 16 h + 4 i + quad, as
+    // the scores have it
+    const int vt_tok = 4 * (r >> 2) + quad;
+    const int vt_swz = 2 * ((vt_tok >> 2) & 3);   // the same for token 16 + vt_tok
+    const bf16x8 ones = as_bf16x8(kv_u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 
     const int last_tile = n_tiles - 1;
     if (t_begin < n_tiles) {
@@ -210,10 +235,12 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                     }
                 float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // m[b] is the same in the four lanes of a column, so each lane can test its own eight
+                // scores against it: the maximum has to cross lanes only on the rare tile that moves it
                 // (with the key range split, a column may have seen no valid key yet: m = -inf)
                 if (__builtin_amdgcn_ballot_w64(mx > m[b] + lag_raw) != 0) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m[b], mx);
                     const float alpha = fast_exp2((m[b] - m_new) * a.scale_log2e);
                     l[b] *= alpha;
@@ -222,36 +249,26 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                     m[b] = m_new;
                 }
                 const float neg_mc = (m[b] == kNegInf) ? 0.f : -m[b] * a.scale_log2e;
-                float p[8], psum = 0.f;
+                float p[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    p[u] = fast_exp2(__builtin_fmaf(sv[u], a.scale_log2e, neg_mc));
-                    psum += p[u];
-                }
-                l[b] += psum;
+                for (int u = 0; u < 8; ++u) p[u] = fast_exp2(__builtin_fmaf(sv[u], a.scale_log2e, neg_mc));
                 pb[b] = as_bf16x8(kv_u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
                                            pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])});
             }
             // ---- O^T += V^T P^T --------------------------------------------------------------------------
-            kv_u32x4 vr[8];  // piece r of token 16 h + 4 i + quad
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int b = 0; b < R; ++b) l[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[b], l[b], 0, 0, 0);
+            const char* vt = reinterpret_cast<const char*>(s_v[buf]) + vt_tok * 256 + (r & 1) * 8;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vr[4 * h + i] = s_v[buf][(16 * h + 4 * i + quad) * 16 + r];
+            for (int j = 0; j < 8; ++j) {
+                // elements [16 j + 4 (r % 4), + 4) of the row: piece 2 j + (r % 4) / 2 (swizzled), half r % 2
+                const int piece_off = ((2 * j + ((r & 3) >> 1)) ^ vt_swz) * 16;
+                const bits16x4 lo = lds_read_transposed(vt + piece_off);
+                const bits16x4 hi = lds_read_transposed(vt + piece_off + 16 * 256);
+                const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                kv_u32x4 lo, hi;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    lo[u] = __builtin_amdgcn_perm(vr[2 * u + 1][w], vr[2 * u][w], 0x05040100u);
-                    hi[u] = __builtin_amdgcn_perm(vr[2 * u + 1][w], vr[2 * u][w], 0x07060302u);
-                }
-#pragma unroll
-                for (int b = 0; b < R; ++b) {
-                    o[b][2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(lo), pb[b], o[b][2 * w], 0, 0, 0);
-                    o[b][2 * w + 1] =
-                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(hi), pb[b], o[b][2 * w + 1], 0, 0, 0);
-                }
+                for (int b = 0; b < R; ++b)
+                    o[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[b], o[b][j], 0, 0, 0);
             }
         }
 
@@ -271,32 +288,26 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     // ---- normalise and store ------------------------------------------------------------------------
 #pragma unroll
     for (int b = 0; b < R; ++b) {
-        float lt = l[b];
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
+        const float lt = l[b][0];
         if (orow[b] >= 0 && a.splits > 1) {
             // partial of this key range: row = index of the output row
             const int64_t rec = (int64_t)split * a.rows + orow[b] / D;
-            float* dst = a.part_o + rec * D + 32 * quad;
+            float* dst = a.part_o + rec * D + 4 * quad;
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                *reinterpret_cast<f32x4*>(dst + 8 * ii) = f32x4{o[b][0][ii], o[b][1][ii], o[b][2][ii], o[b][3][ii]};
-                *reinterpret_cast<f32x4*>(dst + 8 * ii + 4) = f32x4{o[b][4][ii], o[b][5][ii], o[b][6][ii], o[b][7][ii]};
-            }
+            for (int jj = 0; jj < 8; ++jj) *reinterpret_cast<f32x4*>(dst + 16 * jj) = o[b][jj];
             if (quad == 0) {
                 a.part_ml[rec * 2 + 0] = m[b];
                 a.part_ml[rec * 2 + 1] = lt;
             }
         } else if (orow[b] >= 0) {
             const float inv = 1.0f / lt;
-            uint16_t* dst = a.out + orow[b] + 32 * quad;
+            uint16_t* dst = a.out + orow[b] + 4 * quad;
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                kv_u32x4 pk;
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    pk[u] = pack_bf16x2(o[b][2 * u][ii] * inv, o[b][2 * u + 1][ii] * inv);
-                *reinterpret_cast<kv_u32x4*>(dst + 8 * ii) = pk;
+            for (int jj = 0; jj < 8; ++jj) {
+                uint2 pk;
+                pk.x = pack_bf16x2(o[b][jj][0] * inv, o[b][jj][1] * inv);
+                pk.y = pack_bf16x2(o[b][jj][2] * inv, o[b][jj][3] * inv);
+                *reinterpret_cast<uint2*>(dst + 16 * jj) = pk;
             }
         }
     }
