@@ -286,6 +286,32 @@ def test_non_power_of_two_block_size():
         check_close(run_gpu_decode(c, gpu_view(w, triple)), want, f"b12 {triple}")
 
 
+@pytest.mark.parametrize("hq,triple", [(32, (LAYOUT_DP, 1, 0)), (32, (LAYOUT_TP, 2, 1)), (64, (LAYOUT_DP, 1, 0)),
+                                        (32, (LAYOUT_TP, 8, 3)), (32, (LAYOUT_DP, 4, 1))])
+def test_block_capacity_48_on_the_matrix_core_kernels(hq, triple):
+    """B_base = 48 (a multiple of 16 that is no power of two; 96 / 384 tokens per block at TP2 / TP8):
+    the even-split kernels find a tile's block by division.  Shapes for four, two and one head per
+    wavefront; lengths inside one block, at block boundaries and over many blocks."""
+    ctx = np.array([5, 47, 48, 49, 95, 97, 383, 385, 1000, 3000], dtype=np.int32)
+    w = wl.Workload("b48", 33 + hq // 32, hq, 8, 128, 48, len(ctx), "x", ())
+    c = make_case(w, triple, ctx)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+    check_close(run_gpu_decode(c, gpu_view(w, triple)), want, f"b48 {hq} {triple}")
+
+
+@pytest.mark.parametrize("hq,triple", [(32, (LAYOUT_DP, 1, 0)), (64, (LAYOUT_TP, 2, 1)), (32, (LAYOUT_TP, 8, 0))])
+@pytest.mark.parametrize("scale", [1.0, 0.3, 0.002])
+def test_sharp_and_flat_softmax_at_head_dim_128(hq, triple, scale):
+    """scale 1.0 at d = 128 gives logits of +-30 and more: the softmax is nearly one-hot and the
+    reference maximum of the lazily rescaled kernels moves many times per sequence; 0.002 is
+    nearly uniform.  Four, two and one head per wavefront."""
+    ctx = np.array([1, 40, 700, 2500, 33], dtype=np.int32)
+    w = wl.Workload("sharp", 35 + hq // 32, hq, 8, 128, 16, len(ctx), "x", ())
+    c = make_case(w, triple, ctx)
+    want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx, scale)
+    check_close(run_gpu_decode(c, gpu_view(w, triple), scale), want, f"scale {scale} {hq} {triple}")
+
+
 def test_layouts_coexist_in_one_pool_on_gpu():
     """DP-written and TP-written blocks side by side in one pool, two calls (Sec. 5.2.3)."""
     dp_t, tp_t = (LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)
