@@ -32,6 +32,8 @@ namespace {
 
 constexpr int D = 128;
 constexpr int kThreads = 256;
+constexpr int kSub = 2;               // 32-key sub-tiles per staged tile
+constexpr int kKeys = 32 * kSub;      // keys per staged tile (one barrier each)
 
 struct prefill_args {
     const uint16_t* q;      // [total_q][n_q_local][128]
@@ -70,8 +72,8 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 {
     // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)); V pieces at
     // c ^ (2 * ((t / 4) % 4)), which puts the four rows a transposing read touches in different banks
-    __shared__ kv_u32x4 s_k[2][512];
-    __shared__ kv_u32x4 s_v[2][512];
+    __shared__ kv_u32x4 s_k[2][512 * kSub];
+    __shared__ kv_u32x4 s_v[2][512 * kSub];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     if (j0 >= q_len || n <= 0) return;
     const int first_pos = n - q_len;                         // position of the sequence's query 0
     const int j_last = min(j0 + tokens_per_wg, q_len) - 1;   // last query token of this tile
-    const int all_tiles = ((first_pos + j_last) >> 5) + 1;   // key tiles 0 .. all_tiles - 1 of the query tile
+    const int all_tiles = (first_pos + j_last) / kKeys + 1;   // key tiles 0 .. all_tiles - 1 of the query tile
     // this workgroup's share of them: [t_begin, n_tiles)
     const int per_split = (all_tiles + a.splits - 1) / a.splits;
     const int t_begin = split * per_split;
@@ -138,10 +140,10 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     // address of this lane's piece of key row (tile, half h): rows past the end of the sequence
     // are replaced by its last token (finite data, masked later)
     auto piece = [&](int tile, int h) -> const char* {
-        const int hh = min(2 * tile + h, last_half);
+        const int hh = min(2 * kSub * tile + h, last_half);
         const int hb = half_shift >= 0 ? (hh >> half_shift) : hh / halves_per_block;
         const int blk = ids[hb];
-        const int tok = min(32 * tile + 16 * h + ld_row, n - 1);
+        const int tok = min(kKeys * tile + 16 * h + ld_row, n - 1);
         const int slot = tok - hb * v.block_tokens;
         return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot * token_stride_bytes;
     };
@@ -149,10 +151,10 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     // their use and written to LDS one tile ahead, so a whole tile's arithmetic lies between a load
     // and the first wait for it.  Tiles past the last are replaced by the last (loads stay
     // unconditional, so every wait leaves exactly the younger stage in flight).
-    kv_u32x4 stage_k[2][2], stage_v[2][2];
+    kv_u32x4 stage_k[2][2 * kSub], stage_v[2][2 * kSub];
     auto fetch = [&](int stg, int tile) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < 2 * kSub; ++h) {
             const char* p = piece(tile, h);
             // ordinary (cached) loads: every query tile of the sequence reads these keys again
             stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(p);
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     };
     auto stash = [&](int stg, int buf) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < 2 * kSub; ++h) {
             const int row = 16 * h + ld_row;
             s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[stg][h];
             s_v[buf][row * 16 + (ld_c ^ (2 * ((row >> 2) & 3)))] = stage_v[stg][h];
@@ -198,8 +200,12 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     constexpr float kLag = 8.0f;
     const float lag_raw = kLag / a.scale_log2e;
     auto compute = [&](int buf, int tile) {
-        const int base = 32 * tile;
-        if (base <= max_pos) {  // else every key of the tile lies after all of this wavefront's queries
+#pragma unroll
+      for (int sub = 0; sub < kSub; ++sub) {
+        const int base = kKeys * tile + 32 * sub;
+        const kv_u32x4* const sk = s_k[buf] + 512 * sub;
+        const kv_u32x4* const sv = s_v[buf] + 512 * sub;
+        if (base <= max_pos) {  // else every key of the sub-tile lies after all of this wavefront's queries
             // ---- S^T = K q^T ------------------------------------------------------------------------
             f32x4 sacc[R][2];
 #pragma unroll
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    const kv_u32x4 ka = s_k[buf][(16 * h + k_row) * 16 + ((4 * kk + quad) ^ k_row)];
+                    const kv_u32x4 ka = sk[(16 * h + k_row) * 16 + ((4 * kk + quad) ^ k_row)];
 #pragma unroll
                     for (int b = 0; b < R; ++b)
                         sacc[b][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka), qb[b][kk],
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             // ---- O^T += V^T P^T --------------------------------------------------------------------------
 #pragma unroll
             for (int b = 0; b < R; ++b) l[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[b], l[b], 0, 0, 0);
-            const char* vt = reinterpret_cast<const char*>(s_v[buf]) + vt_tok * 256 + (r & 1) * 8;
+            const char* vt = reinterpret_cast<const char*>(sv) + vt_tok * 256 + (r & 1) * 8;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 // elements [16 j + 4 (r % 4), + 4) of the row: piece 2 j + (r % 4) / 2 (swizzled), half r % 2
@@ -271,7 +277,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                     o[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[b], o[b][j], 0, 0, 0);
             }
         }
-
+      }
     };
     for (int tile = t_begin; tile < n_tiles; tile += 2) {
         fetch(0, min(tile + 2, last_tile));
@@ -354,7 +360,7 @@ int prefill_splits(const kv_view* view, int batch, int max_ctx_len, int max_q_le
     const int64_t wgs = (int64_t)((max_q_len + tokens_per_wg - 1) / tokens_per_wg) * view->n_kv_local * batch;
     if (wgs >= 512) return 1;
     int s = (int)((768 + wgs - 1) / wgs);
-    const int most = max_ctx_len / (32 * 16);
+    const int most = max_ctx_len / 512;
     if (s > most) s = most;
     if (s > 16) s = 16;
     return s < 1 ? 1 : s;
