@@ -283,7 +283,7 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
                        const kv_view* other_view, const int32_t* other_table,
                        int64_t other_stride, void* hip_stream);
 
-/* Tunables for experiments and tests (process-wide; 0 = automatic for all of them):
+/* Tunables for experiments and tests (process-wide; 0 = automatic unless stated otherwise):
  *   "chunk_tokens"  split-KV granularity of the chunked decode kernels, a multiple of 64
  *   "force_kernel"  decode kernel: 1 even split over resident wavefronts, 2 vector ALU, 3 chunked
  *                   matrix-core (KV_ERR_UNSUPPORTED from the call if the shape is not served)
@@ -292,6 +292,8 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
  *                   instead of through LDS, bit 1 no register double buffering (both for the
  *                   one-head-per-wavefront kernel), bit 2 one KV head per wavefront even where
  *                   several adjacent heads per wavefront are possible
+ *   "xcd_skew"      even-split decode kernels: share moved from each odd-numbered to each even-numbered
+ *                   XCD, in 1/1024 of an even share (0..256; -1 = the library's default, 64)
  *   "linear_splits" workgroups sharing the input dimension of one output tile in kv_linear_view
  *                   (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
  *                   follows the option, so size the workspace after setting it

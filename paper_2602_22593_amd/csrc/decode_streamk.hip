@@ -4,14 +4,15 @@
 // wavefront, described where it is defined); kv_streamk_launch picks one per view.
 //
 // The batch is flattened into tiles of 32 tokens of one (sequence, local KV head) pair, pairs
-// ordered (sequence, head) with the head fastest.  With T tiles in total and W wavefronts
-// launched, wavefront w owns tiles [w * ceil(T / W), (w + 1) * ceil(T / W)): every wavefront
-// streams the same number of KV bytes whatever the mix of context lengths, and lives long
-// enough to amortise its start-up (the grid is sized so that all W wavefronts are resident at
-// once).  A wavefront's range may cover the end of one pair and the start of the next; each
-// (wavefront, pair) piece yields either the final output row (the piece is the whole pair) or an
-// un-normalised partial (m, l, acc[G][d]) in workspace slot w + pair_index, which is unique
-// and keeps the pieces of a pair in consecutive slots for the merge kernel.
+// ordered (sequence, head) with the head fastest.  The T tiles are cut into W consecutive ranges,
+// one per launched wavefront (the grid is sized so that all W are resident at once), of nearly
+// equal length (a small, fixed correction per XCD, see split_prologue): every wavefront streams
+// about the same number of KV bytes whatever the mix of context lengths, and lives long enough
+// to amortise its start-up.  A wavefront's range may cover the end of one pair and the start of
+// the next; each (wavefront, pair) piece yields either the final output row (the piece is the
+// whole pair) or an un-normalised partial (m, l, acc[G][d]) in workspace slot w + pair_index,
+// which is unique and keeps the pieces of a pair in consecutive slots; the wavefronts holding a
+// pair's first and last piece leave their numbers in the pair's descriptor for the merge kernel.
 //
 // Per tile, lane l = (r = l % 16, quad = l / 16).  Both products put the KV data in the MFMA
 // A operand (row index r) and the query group, padded to 16, in the B operand (column r = g):
@@ -33,6 +34,8 @@ constexpr int kSkThreads = 256;
 constexpr int kSkWaves = kSkThreads / 64;
 constexpr int kMaxBatch = KV_STREAMK_MAX_BATCH;
 constexpr int D = 128;
+constexpr int kMaxClasses = 8;
+constexpr int kDefaultXcdSkew = 64;
 
 struct tile_regs {
     kv_u32x4 k[2][4];  // [half][kk]
@@ -244,17 +247,50 @@ __device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pai
         }
         if (tid == kSkThreads - 1) s_prefix[a.batch] = before + incl;
         __syncthreads();
-        // the merge kernel needs the same numbers: the first workgroup leaves them in the workspace
-        if (blockIdx.x == 0)
-            for (int k = tid; k <= a.batch; k += kSkThreads) a.prefix_out[k] = s_prefix[k];
     }
 
+    // Wavefront w = 4 * workgroup + wave owns the w-th range in tile order.  The ranges are not all
+    // of one length: the hardware deals consecutive workgroups out to the XCDs in turn, workgroup b
+    // runs on XCD b % 8, and a wavefront's share is proportional to the weight of its XCD.  Range
+    // w starts at tile floor(total * W(w) / W(n_waves)), W(w) the summed weight of the wavefronts
+    // before w (in double precision, with the reciprocal from the host: any monotone function that
+    // every wavefront evaluates alike cuts the tiles into disjoint ranges; the ends are pinned).
     const int total = uniform(s_prefix[a.batch]) * pairs;
-    const int tpw = (total + a.n_waves - 1) / a.n_waves;
+    auto range_start = [&](int w) -> int {
+        if (w >= a.n_waves) return total;
+        const int grp = w / (kMaxClasses * kSkWaves), in_grp = w % (kMaxClasses * kSkWaves);
+        const int x = in_grp / kSkWaves, i = in_grp % kSkWaves;   // XCD of the workgroup, wave in it
+        const uint32_t before = (uint32_t)grp * (kSkWaves * a.wt_prefix[kMaxClasses]) + kSkWaves * a.wt_prefix[x] +
+                                (uint32_t)i * (a.wt_prefix[x + 1] - a.wt_prefix[x]);
+        return min((int)((double)total * ((double)before * a.inv_weight)), total);
+    };
     sp.w = blockIdx.x * kSkWaves + wave;
-    sp.x0 = sp.w * tpw;
-    sp.x1 = min(sp.x0 + tpw, total);
-    if (sp.x0 >= sp.x1) return false;
+    sp.x0 = range_start(sp.w);
+    sp.x1 = range_start(sp.w + 1);
+    const int b1 = sp.x1;
+    if (sp.x0 >= sp.x1) {
+        // Fewer tiles than wavefronts.  A pair cut between the neighbouring wavefronts lists this
+        // one among its pieces: leave an empty partial (m = -inf, l = 0, zeros) in the slot the
+        // merge kernel will look at.
+        if (b1 > 0) {
+            const int x = b1 - 1;
+            int lo = 0, hi = a.batch;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (uniform(s_prefix[mid]) * pairs <= x) lo = mid; else hi = mid;
+            }
+            const int ts = uniform(s_prefix[lo + 1]) - uniform(s_prefix[lo]);
+            const int pr = (x - uniform(s_prefix[lo]) * pairs) / ts;
+            const int64_t slot = (int64_t)sp.w + (int64_t)lo * pairs + pr;
+            if (lane < a.cols) {
+                a.part_ml[(slot * a.cols + lane) * 2 + 0] = kNegInf;
+                a.part_ml[(slot * a.cols + lane) * 2 + 1] = 0.f;
+            }
+            float* acc = a.part_acc + slot * a.cols * D;
+            for (int e = lane; e < a.cols * D; e += 64) acc[e] = 0.f;
+        }
+        return false;
+    }
 
     // sequence holding tile x0: largest s with prefix[s] * pairs <= x0
     {
@@ -273,7 +309,7 @@ __device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pai
 }
 
 template <int KMODE, int PIPE, bool MIXED>
-__global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kernel(kv_streamk_args a)
+__global__ __launch_bounds__(kSkThreads, PIPE ? 1 : 2) void decode_streamk_kernel(kv_streamk_args a)
 {
     __shared__ kv_u32x4 s_kstage[KMODE == 1 ? kSkWaves * 512 : 1];
     __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
@@ -406,6 +442,12 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 2 : 3) void decode_streamk_kerne
         st.l += __shfl_xor(st.l, 16);
         st.l += __shfl_xor(st.l, 32);
         const bool whole = (tile == 0 && seg_end == tiles_s);
+        // first and last piece of the pair tell the merge kernel where its pieces lie
+        if (lane == 0) {
+            int32_t* desc = a.pair_desc + ((int64_t)s * Hl + hl) * 2;
+            if (tile == 0) desc[0] = w;
+            if (seg_end == tiles_s) desc[1] = w;
+        }
         if (lc.r < G) {
             if (whole) {
                 const float inv = 1.0f / st.l;
@@ -705,6 +747,11 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
         st.l += __shfl_xor(st.l, 32);
         const float m_col = __shfl(st.m, wl.src);
         const bool whole = (tile == 0 && seg_end == tiles_s);
+        if (lane == 0) {
+            int32_t* desc = a.pair_desc + ((int64_t)s * P + hg) * 2;
+            if (tile == 0) desc[0] = w;
+            if (seg_end == tiles_s) desc[1] = w;
+        }
         if (wl.r < C) {
             if (whole) {
                 const float inv = 1.0f / st.l;
@@ -754,8 +801,9 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
 // kMergeSplit workgroups, each owning 128 / kMergeSplit columns as 8 column groups x 32 slices.
 // The host launches kMergeSplit workgroups per row only when the batch has few pairs for the
 // wavefronts launched (long lists are then the rule); in such a grid all but the first leave at
-// once for a short list.  Recomputes the split exactly as the main kernel did, from the per-sequence tile
-// prefix that kernel left behind.
+// once for a short list.  Which slots hold the pieces of a pair is read from the pair's descriptor:
+// the numbers of the wavefronts that held its first and its last piece, left by the main kernel,
+// so this kernel does not depend on how the tiles were cut.
 constexpr int kMergeSplit = 4;
 constexpr int kMergeLong = 24;  // pieces from which a list counts as long
 __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_args a)
@@ -766,23 +814,18 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     __shared__ float s_max[32];
     __shared__ float s_acc[8 * D];
     __shared__ float s_l[32];
-    // tiles before sequence s and in total, as computed by the main kernel
-    const int before = a.prefix_out[s];
-    const int all = a.prefix_out[a.batch];
-
     const int n = a.ctx_lens[s];
     uint16_t* dst = a.out + ((int64_t)s * v.n_q_local + qi) * D;
+    const int hl = qi / G, g = qi - hl * G;
+    // numbers of the wavefronts that held the pair's first and last piece, left by the main kernel
+    const int2 ends = *reinterpret_cast<const int2*>(a.pair_desc + ((int64_t)s * Hl + hl) * 2);
     if (n == 0) {
         if (z == 0 && tid < D) dst[tid] = 0;
         return;
     }
-    const int tiles_s = (n + (1 << a.tile_shift) - 1) >> a.tile_shift;
-    const int hl = qi / G, g = qi - hl * G;
-    const int total = all * Hl;
-    const int tpw = (total + a.n_waves - 1) / a.n_waves;
-    const int p0 = before * Hl + hl * tiles_s;          // first tile of the pair, flattened
-    const int w_first = p0 / tpw, w_last = (p0 + tiles_s - 1) / tpw;
-    if (w_first == w_last) return;                      // written in place by the main kernel
+    // (clamped: whatever the words hold, the slots read below lie inside the workspace)
+    const int w_first = min(max(ends.x, 0), a.n_waves - 1), w_last = min(ends.y, a.n_waves - 1);
+    if (w_first >= w_last) return;                      // one piece: written in place by the main kernel
     const bool wide = (gridDim.z > 1 && w_last - w_first + 1 >= kMergeLong);
     if (!wide && z != 0) return;
     const int64_t pair = (int64_t)s * Hl + hl;
@@ -799,8 +842,10 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
         const int64_t rec = (w + pair) * G + g;
         const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
         const f32x4 part = *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4);
-        const float mn = fmaxf(mr, ml.x);          // finite: every piece holds a valid token
-        const float c_old = fast_exp2(mr - mn), c_new = fast_exp2(ml.x - mn);
+        // (a wavefront that had no tiles left m = -inf, l = 0 and zeros: its weight comes out as 0)
+        const float mn = fmaxf(mr, ml.x);
+        const float ref = (mn == kNegInf) ? 0.f : mn;
+        const float c_old = fast_exp2(mr - ref), c_new = fast_exp2(ml.x - ref);
         ll = ll * c_old + ml.y * c_new;
         acc = acc * c_old + part * c_new;
         mr = mn;
@@ -858,8 +903,9 @@ size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves)
         workspace_layout(view, batch, n_waves, hpw, acc, ml);
         if (acc + ml > need) need = acc + ml;
     }
-    const size_t prefix = ((size_t)(batch + 1) * 4 + 255) / 256 * 256;
-    return need + prefix;
+    // pair descriptors: two wavefront numbers per (sequence, pair)
+    const size_t desc = ((size_t)batch * view->n_kv_local * 2 * 4 + 255) / 256 * 256;
+    return need + desc;
 }
 
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st)
@@ -873,7 +919,21 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     workspace_layout(view, a.batch, a.n_waves, hpw, acc, ml);
     a.part_acc = (float*)workspace;
     a.part_ml = (float*)((char*)workspace + acc);
-    a.prefix_out = (int32_t*)((char*)workspace + acc + ml);
+    a.pair_desc = (int32_t*)((char*)workspace + acc + ml);
+    // Weights of the XCDs.  Under this kernel's load the odd-numbered XCDs stream slower than the
+    // even-numbered ones (their wavefronts end 8-13 % later on every workload measured), so
+    // `skew` / 1024 of an even share is moved from each odd to each even one.  The workgroup ->
+    // XCD rule only holds for whole rounds of eight workgroups; otherwise all weigh the same.
+    {
+        int64_t skew = kv_option_xcd_skew();
+        if (skew < 0) skew = kDefaultXcdSkew;
+        if ((a.n_waves / kSkWaves) % kMaxClasses != 0) skew = 0;
+        a.wt_prefix[0] = 0;
+        for (int x = 0; x < kMaxClasses; ++x)
+            a.wt_prefix[x + 1] = a.wt_prefix[x] + (uint32_t)(1024 + ((x & 1) ? -skew : skew));
+        // total weight = n_waves * 1024 in both cases (the skews of a round of eight cancel)
+        a.inv_weight = 1.0 / ((double)a.n_waves * 1024.0);
+    }
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
     if (hpw == 4) {

@@ -83,6 +83,7 @@ int64_t kv_option_chunk_tokens();
 int64_t kv_option_force_kernel();
 int64_t kv_option_waves_per_cu();
 int64_t kv_option_variant();
+int64_t kv_option_xcd_skew();  // -1: library default; else 0..256 in 1/1024 of an even share
 int64_t kv_option_linear_splits();
 
 // Per-kernel event brackets for kv_profile_*: begin returns a slot (or -1 when disabled).
@@ -111,7 +112,7 @@ struct kv_streamk_args {
     int32_t n_waves;   // wavefronts launched (multiple of 4)
     float* part_acc;   // [n_waves + batch * n_kv_local][group][128]
     float* part_ml;    // [n_waves + batch * n_kv_local][group][2]
-    int32_t* prefix_out;  // [batch + 1] tiles of the sequences before s, written by the main kernel
+    int32_t* pair_desc;   // [batch * pairs][2] numbers of the wavefronts holding a pair's first and last piece
     const int32_t* view_ids;  // [batch] index into lay[] per sequence, or null: every sequence under v
     int32_t n_views;
     kv_layout_dev lay[KV_MAX_MIXED_VIEWS];
@@ -121,6 +122,9 @@ struct kv_streamk_args {
     int32_t pairs;           // pairs per sequence = n_kv_local / heads_per_wave
     int32_t cols;            // output rows per pair = heads_per_wave * group (<= 16)
     int32_t tile_shift;      // 5 (one head), 4 (two heads) or 3 (four heads)
+    uint32_t wt_prefix[9];   // wt_prefix[x] = summed weight of XCDs < x; a wavefront's share of the tiles
+                             // is proportional to the weight of the XCD its workgroup runs on
+    double inv_weight;       // 1 / (summed weight of all wavefronts)
 };
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

@@ -23,12 +23,14 @@ static std::atomic<int64_t> g_chunk_tokens{0};
 static std::atomic<int64_t> g_force_kernel{0};
 static std::atomic<int64_t> g_waves_per_cu{0};
 static std::atomic<int64_t> g_variant{0};
+static std::atomic<int64_t> g_xcd_skew{-1};
 static std::atomic<int64_t> g_linear_splits{0};
 
 int64_t kv_option_chunk_tokens() { return g_chunk_tokens.load(); }
 int64_t kv_option_force_kernel() { return g_force_kernel.load(); }
 int64_t kv_option_waves_per_cu() { return g_waves_per_cu.load(); }
 int64_t kv_option_variant() { return g_variant.load(); }
+int64_t kv_option_xcd_skew() { return g_xcd_skew.load(); }
 int64_t kv_option_linear_splits() { return g_linear_splits.load(); }
 
 // ---- per-kernel event brackets -----------------------------------------------------------
@@ -188,6 +190,11 @@ int kv_set_option(const char* key, int64_t value)
         g_linear_splits.store(value);
         return KV_OK;
     }
+    if (!strcmp(key, "xcd_skew")) {
+        if (value < -1 || value > 256) return KV_ERR_INVALID_ARG;
+        g_xcd_skew.store(value);
+        return KV_OK;
+    }
     if (!strcmp(key, "waves_per_cu")) {
         if (value < 0 || value > 32 || (value % 4) != 0) return KV_ERR_INVALID_ARG;
         g_waves_per_cu.store(value);
@@ -203,6 +210,7 @@ int64_t kv_get_option(const char* key)
     if (!strcmp(key, "force_kernel")) return g_force_kernel.load();
     if (!strcmp(key, "waves_per_cu")) return g_waves_per_cu.load();
     if (!strcmp(key, "variant")) return g_variant.load();
+    if (!strcmp(key, "xcd_skew")) return g_xcd_skew.load();
     if (!strcmp(key, "linear_splits")) return g_linear_splits.load();
     return -1;
 }

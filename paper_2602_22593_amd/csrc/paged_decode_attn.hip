@@ -562,7 +562,7 @@ static int launch_streamk(const void* q, void* out, const void* kv_pool, const i
     k.n_waves = n_waves;
     k.part_acc = nullptr;
     k.part_ml = nullptr;
-    k.prefix_out = nullptr;
+    k.pair_desc = nullptr;
     k.view_ids = view_ids;
     k.n_views = view_ids ? n_views : 1;
     for (int i = 0; i < KV_MAX_MIXED_VIEWS; ++i) {

@@ -238,6 +238,18 @@ def test_strerror_and_options():
     with pytest.raises(kv.KVError):
         kv.kv_set_option("no_such_option", 1)
     kv.kv_set_option("chunk_tokens", 0)
+    # the share moved between XCDs: -1 (library default) .. 256; the input splits of kv_linear_view: 0 .. 16
+    assert kv.kv_get_option("xcd_skew") == -1
+    kv.kv_set_option("xcd_skew", 256)
+    assert kv.kv_get_option("xcd_skew") == 256
+    for bad in (-2, 257):
+        with pytest.raises(kv.KVError):
+            kv.kv_set_option("xcd_skew", bad)
+    kv.kv_set_option("xcd_skew", -1)
+    kv.kv_set_option("linear_splits", 16)
+    with pytest.raises(kv.KVError):
+        kv.kv_set_option("linear_splits", 17)
+    kv.kv_set_option("linear_splits", 0)
 
 
 def test_product_package_does_not_import_the_oracle():

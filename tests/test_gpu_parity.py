@@ -162,6 +162,27 @@ def test_long_sequences_cut_over_every_wavefront_head_groups():
     check_close(got, want, "long sequence, head groups")
 
 
+@pytest.mark.parametrize("skew", [0, 100, 256])
+def test_uneven_shares_between_xcds(skew):
+    """The split gives wavefronts on even- and odd-numbered XCDs ranges of different length; 256 is
+    the largest the option allows (5 : 3).  Few tiles (most wavefronts have none, and pairs are cut
+    between wavefronts that have neighbours without tiles) and many (every wavefront busy), with
+    four heads and one head per wavefront."""
+    kv.kv_set_option("xcd_skew", skew)
+    try:
+        for lens in ([1, 31, 32, 33, 0, 511, 513, 4100, 2049, 64, 7000, 96], [20000, 17, 9000, 12345, 0, 700],
+                     [3, 0, 9]):
+            lens = np.array(lens, dtype=np.int32)
+            for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 8, 5)]:
+                w = wl.Workload("shares", 72, 32, 8, 128, 16, len(lens), "x", ())
+                c = make_case(w, triple, lens)
+                want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+                got = run_gpu_decode(c, gpu_view(w, triple))
+                check_close(got, want, f"skew {skew} {triple} {len(lens)} sequences")
+    finally:
+        kv.kv_set_option("xcd_skew", -1)
+
+
 def test_one_long_sequence_cut_over_every_wavefront():
     """A single (sequence, head) pair cut over every wavefront of the launch (about a thousand
     pieces to merge), twice in a row on one uninitialised workspace, which then serves a call of
