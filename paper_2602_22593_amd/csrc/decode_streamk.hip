@@ -36,6 +36,7 @@ constexpr int kMaxBatch = KV_STREAMK_MAX_BATCH;
 constexpr int D = 128;
 constexpr int kMaxClasses = 8;
 constexpr int kDefaultXcdSkew = 64;
+constexpr int kDefaultPieceUnits = 8;   // start of a pair, in eighths of a tile
 
 struct tile_regs {
     kv_u32x4 k[2][4];  // [half][kk]
@@ -206,67 +207,141 @@ struct split_pos {
     int x0, x1, s, tiles_s, pair, tile, w;
 };
 
-// Common start of the even-split kernels (whole workgroup): exclusive prefix sum of the tiles
-// (2^TSHIFT tokens) per sequence into s_prefix, context lengths into s_ctx, then this
-// wavefront's share and the position of its first tile.  False: the wavefront has no tiles.
+constexpr int kTileUnits = 8;   // weight of a tile on the axis that is cut; a pair's start weighs a.piece_units
+
+// Common start of the even-split kernels (whole workgroup): exclusive prefix sums over the sequences
+// of the tiles (2^TSHIFT tokens) into s_prefix and of the non-empty sequences into s_ne, context
+// lengths into s_ctx, then this wavefront's share and the position of its first tile.  False: the
+// wavefront has no tiles.
+//
+// What is cut evenly is not the tile axis itself but a weighted one, on which a tile is kTileUnits
+// long and the start of every pair adds a.piece_units: a wavefront that has to close one piece
+// and open another (write a partial, fetch new query rows and block ids, refill its load
+// pipeline) gets that much less to stream.  Position u of the weighted axis maps to a tile by
+// tile_at(), a monotone function that every wavefront evaluates alike, so the ranges
+// [tile_at(u(w)), tile_at(u(w + 1))) are disjoint and cover all tiles.
 template <int TSHIFT>
 __device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pairs, int32_t* s_prefix,
-                                               int32_t* s_ctx, int32_t* s_wsum, split_pos& sp)
+                                               int32_t* s_ne, int32_t* s_ctx, int32_t* s_wsum, split_pos& sp)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
     {
         const int per = (a.batch + kSkThreads - 1) / kSkThreads;
         const int s0 = tid * per;
-        int local = 0;
+        int local = 0, local_ne = 0;
         for (int k = 0; k < per; ++k) {
             const int s = s0 + k;
             if (s < a.batch) {
                 const int c = a.ctx_lens[s];
                 s_ctx[s] = c;
                 local += (c + (1 << TSHIFT) - 1) >> TSHIFT;
+                local_ne += c > 0 ? 1 : 0;
             }
         }
-        int incl = local;
+        int incl = local, incl_ne = local_ne;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const int up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
+            const int up = __shfl_up(incl, off), up_ne = __shfl_up(incl_ne, off);
+            if (lane >= off) {
+                incl += up;
+                incl_ne += up_ne;
+            }
         }
-        if (lane == 63) s_wsum[wave] = incl;
+        if (lane == 63) {
+            s_wsum[wave] = incl;
+            s_wsum[kSkWaves + wave] = incl_ne;
+        }
         __syncthreads();
-        int before = 0;
-        for (int w = 0; w < wave; ++w) before += s_wsum[w];
-        int run = before + incl - local;
+        int before = 0, before_ne = 0;
+        for (int w = 0; w < wave; ++w) {
+            before += s_wsum[w];
+            before_ne += s_wsum[kSkWaves + w];
+        }
+        int run = before + incl - local, run_ne = before_ne + incl_ne - local_ne;
         for (int k = 0; k < per; ++k) {
             const int s = s0 + k;
             if (s < a.batch) {
                 s_prefix[s] = run;
+                s_ne[s] = run_ne;
                 run += (s_ctx[s] + (1 << TSHIFT) - 1) >> TSHIFT;
+                run_ne += s_ctx[s] > 0 ? 1 : 0;
             }
         }
-        if (tid == kSkThreads - 1) s_prefix[a.batch] = before + incl;
+        if (tid == kSkThreads - 1) {
+            s_prefix[a.batch] = before + incl;
+            s_ne[a.batch] = before_ne + incl_ne;
+        }
         __syncthreads();
     }
 
-    // Wavefront w = 4 * workgroup + wave owns the w-th range in tile order.  The ranges are not all
-    // of one length: the hardware deals consecutive workgroups out to the XCDs in turn, workgroup b
-    // runs on XCD b % 8, and a wavefront's share is proportional to the weight of its XCD.  Range
-    // w starts at tile floor(total * W(w) / W(n_waves)), W(w) the summed weight of the wavefronts
-    // before w (in double precision, with the reciprocal from the host: any monotone function that
-    // every wavefront evaluates alike cuts the tiles into disjoint ranges; the ends are pinned).
     const int total = uniform(s_prefix[a.batch]) * pairs;
-    auto range_start = [&](int w) -> int {
-        if (w >= a.n_waves) return total;
+    const uint32_t cu = (uint32_t)a.piece_units;
+    // weighted position of the first tile of sequence sq
+    auto wpos = [&](int sq) -> unsigned long long {
+        return (unsigned long long)pairs *
+               ((unsigned long long)kTileUnits * (uint32_t)uniform(s_prefix[sq]) + (unsigned long long)cu * (uint32_t)uniform(s_ne[sq]));
+    };
+    auto wpos_lane = [&](int sq) -> unsigned long long {   // the same for an index that differs per lane
+        return (unsigned long long)pairs *
+               ((unsigned long long)kTileUnits * (uint32_t)s_prefix[sq] + (unsigned long long)cu * (uint32_t)s_ne[sq]);
+    };
+    const unsigned long long u_all = wpos(a.batch);
+    // Wavefront w = 4 * workgroup + wave owns the w-th range.  The ranges are not all of one
+    // weighted length either: the hardware deals consecutive workgroups out to the XCDs in turn,
+    // workgroup b runs on XCD b % 8, and a wavefront's share is proportional to the weight of its
+    // XCD.  Range w starts at weighted position floor(u_all * W(w) / W(n_waves)), W(w) the summed
+    // weight of the wavefronts before w (in double precision, with the reciprocal from the host).
+    auto range_u = [&](int w) -> unsigned long long {
+        if (w >= a.n_waves) return u_all;
         const int grp = w / (kMaxClasses * kSkWaves), in_grp = w % (kMaxClasses * kSkWaves);
         const int x = in_grp / kSkWaves, i = in_grp % kSkWaves;   // XCD of the workgroup, wave in it
         const uint32_t before = (uint32_t)grp * (kSkWaves * a.wt_prefix[kMaxClasses]) + kSkWaves * a.wt_prefix[x] +
                                 (uint32_t)i * (a.wt_prefix[x + 1] - a.wt_prefix[x]);
-        return min((int)((double)total * ((double)before * a.inv_weight)), total);
+        const unsigned long long u = (unsigned long long)((double)u_all * ((double)before * a.inv_weight));
+        return u < u_all ? u : u_all;
+    };
+    // tile holding weighted position u: its number on the flattened tile axis and where it lies
+    struct tile_pos {
+        int x, s, tiles_s, pair, tile;
+    };
+    auto tile_at = [&](unsigned long long u) -> tile_pos {
+        tile_pos t;
+        if (u >= u_all) {
+            t.x = total;
+            t.s = a.batch;
+            t.tiles_s = 1;
+            t.pair = t.tile = 0;
+            return t;
+        }
+        // largest s with wpos(s) <= u (a non-empty sequence, since u < u_all), by a 64-way search:
+        // every lane probes one sequence, a ballot counts the probes not above u (wpos is monotone)
+        const int chunk = (a.batch + 63) >> 6;
+        int lo = 0;
+        {
+            const int probe = lane * chunk;
+            const bool ok = probe < a.batch && wpos_lane(probe) <= u;
+            lo = (__builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)) - 1) * chunk;   // lane 0 always counts
+        }
+        if (chunk > 1) {
+            const int probe = lo + lane;
+            const bool ok = lane < chunk && probe < a.batch && wpos_lane(probe) <= u;
+            lo += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)) - 1;
+        }
+        t.s = lo;
+        t.tiles_s = uniform(s_prefix[lo + 1]) - uniform(s_prefix[lo]);
+        const uint32_t rel = (uint32_t)(u - wpos(lo));                       // < pairs * len: fits (host check)
+        const uint32_t len = (uint32_t)kTileUnits * (uint32_t)t.tiles_s + cu;  // weighted length of a pair
+        t.pair = (int)(rel / len);
+        const uint32_t r = rel - (uint32_t)t.pair * len;
+        t.tile = r < cu ? 0 : (int)((r - cu) / kTileUnits);
+        t.x = uniform(s_prefix[lo]) * pairs + t.pair * t.tiles_s + t.tile;
+        return t;
     };
     sp.w = blockIdx.x * kSkWaves + wave;
-    sp.x0 = range_start(sp.w);
-    sp.x1 = range_start(sp.w + 1);
+    const tile_pos first = tile_at(range_u(sp.w));
+    sp.x0 = first.x;
+    sp.x1 = tile_at(range_u(sp.w + 1)).x;
     const int b1 = sp.x1;
     if (sp.x0 >= sp.x1) {
         // Fewer tiles than wavefronts.  A pair cut between the neighbouring wavefronts lists this
@@ -291,20 +366,10 @@ __device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pai
         }
         return false;
     }
-
-    // sequence holding tile x0: largest s with prefix[s] * pairs <= x0
-    {
-        int lo = 0, hi = a.batch;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (uniform(s_prefix[mid]) * pairs <= sp.x0) lo = mid; else hi = mid;
-        }
-        sp.s = lo;
-    }
-    sp.tiles_s = uniform(s_prefix[sp.s + 1]) - uniform(s_prefix[sp.s]);
-    const int rem = sp.x0 - uniform(s_prefix[sp.s]) * pairs;
-    sp.pair = rem / sp.tiles_s;
-    sp.tile = rem - sp.pair * sp.tiles_s;
+    sp.s = first.s;
+    sp.tiles_s = first.tiles_s;
+    sp.pair = first.pair;
+    sp.tile = first.tile;
     return true;
 }
 
@@ -314,7 +379,8 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 1 : 2) void decode_streamk_kerne
     __shared__ kv_u32x4 s_kstage[KMODE == 1 ? kSkWaves * 512 : 1];
     __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
     __shared__ int32_t s_ctx[kMaxBatch];
-    __shared__ int32_t s_wsum[kSkWaves];
+    __shared__ int32_t s_ne[kMaxBatch + 1];      // non-empty sequences before s
+    __shared__ int32_t s_wsum[2 * kSkWaves];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
@@ -322,7 +388,7 @@ __global__ __launch_bounds__(kSkThreads, PIPE ? 1 : 2) void decode_streamk_kerne
     const int Hl = v.n_kv_local, G = a.group;
 
     split_pos sp;
-    if (!split_prologue<5>(a, Hl, s_prefix, s_ctx, s_wsum, sp)) return;
+    if (!split_prologue<5>(a, Hl, s_prefix, s_ne, s_ctx, s_wsum, sp)) return;
     int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hl = sp.pair, tile = sp.tile;
     const int x1 = sp.x1, w = sp.w;
 
@@ -635,7 +701,8 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
     __shared__ kv_u32x4 s_kstage[kSkWaves * 512];
     __shared__ int32_t s_prefix[kMaxBatch + 1];  // tiles of the sequences before s
     __shared__ int32_t s_ctx[kMaxBatch];
-    __shared__ int32_t s_wsum[kSkWaves];
+    __shared__ int32_t s_ne[kMaxBatch + 1];      // non-empty sequences before s
+    __shared__ int32_t s_wsum[2 * kSkWaves];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
@@ -643,7 +710,7 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
     const int P = a.pairs, C = a.cols, G = a.group;
 
     split_pos sp;
-    if (!split_prologue<TSHIFT>(a, P, s_prefix, s_ctx, s_wsum, sp)) return;
+    if (!split_prologue<TSHIFT>(a, P, s_prefix, s_ne, s_ctx, s_wsum, sp)) return;
     int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hg = sp.pair, tile = sp.tile;
     const int x1 = sp.x1, w = sp.w;
 
@@ -933,6 +1000,8 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
             a.wt_prefix[x + 1] = a.wt_prefix[x] + (uint32_t)(1024 + ((x & 1) ? -skew : skew));
         // total weight = n_waves * 1024 in both cases (the skews of a round of eight cancel)
         a.inv_weight = 1.0 / ((double)a.n_waves * 1024.0);
+        const int64_t pc = kv_option_piece_cost();
+        a.piece_units = (int32_t)(pc < 0 ? kDefaultPieceUnits : pc);
     }
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);

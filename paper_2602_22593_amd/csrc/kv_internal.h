@@ -83,6 +83,7 @@ int64_t kv_option_chunk_tokens();
 int64_t kv_option_force_kernel();
 int64_t kv_option_waves_per_cu();
 int64_t kv_option_variant();
+int64_t kv_option_piece_cost();  // -1: library default; else 0..64 eighths of a tile
 int64_t kv_option_xcd_skew();  // -1: library default; else 0..256 in 1/1024 of an even share
 int64_t kv_option_linear_splits();
 
@@ -125,6 +126,7 @@ struct kv_streamk_args {
     uint32_t wt_prefix[9];   // wt_prefix[x] = summed weight of XCDs < x; a wavefront's share of the tiles
                              // is proportional to the weight of the XCD its workgroup runs on
     double inv_weight;       // 1 / (summed weight of all wavefronts)
+    int32_t piece_units;     // weight of the start of a pair on the axis that is cut, a tile weighing 8
 };
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

@@ -24,6 +24,7 @@ static std::atomic<int64_t> g_force_kernel{0};
 static std::atomic<int64_t> g_waves_per_cu{0};
 static std::atomic<int64_t> g_variant{0};
 static std::atomic<int64_t> g_xcd_skew{-1};
+static std::atomic<int64_t> g_piece_cost{-1};
 static std::atomic<int64_t> g_linear_splits{0};
 
 int64_t kv_option_chunk_tokens() { return g_chunk_tokens.load(); }
@@ -31,6 +32,7 @@ int64_t kv_option_force_kernel() { return g_force_kernel.load(); }
 int64_t kv_option_waves_per_cu() { return g_waves_per_cu.load(); }
 int64_t kv_option_variant() { return g_variant.load(); }
 int64_t kv_option_xcd_skew() { return g_xcd_skew.load(); }
+int64_t kv_option_piece_cost() { return g_piece_cost.load(); }
 int64_t kv_option_linear_splits() { return g_linear_splits.load(); }
 
 // ---- per-kernel event brackets -----------------------------------------------------------
@@ -190,6 +192,11 @@ int kv_set_option(const char* key, int64_t value)
         g_linear_splits.store(value);
         return KV_OK;
     }
+    if (!strcmp(key, "piece_cost")) {
+        if (value < -1 || value > 64) return KV_ERR_INVALID_ARG;
+        g_piece_cost.store(value);
+        return KV_OK;
+    }
     if (!strcmp(key, "xcd_skew")) {
         if (value < -1 || value > 256) return KV_ERR_INVALID_ARG;
         g_xcd_skew.store(value);
@@ -211,6 +218,7 @@ int64_t kv_get_option(const char* key)
     if (!strcmp(key, "waves_per_cu")) return g_waves_per_cu.load();
     if (!strcmp(key, "variant")) return g_variant.load();
     if (!strcmp(key, "xcd_skew")) return g_xcd_skew.load();
+    if (!strcmp(key, "piece_cost")) return g_piece_cost.load();
     if (!strcmp(key, "linear_splits")) return g_linear_splits.load();
     return -1;
 }

@@ -543,6 +543,9 @@ static int launch_streamk(const void* q, void* out, const void* kv_pool, const i
     // tiles (of 8 tokens at the least) over all (sequence, head) pairs must fit 31 bits
     if (((int64_t)max_ctx_len / 8 + 1) * batch * view->n_kv_local >= ((int64_t)1 << 31))
         return KV_ERR_UNSUPPORTED;
+    // and the weighted length of one sequence's pairs (8 units per tile plus a cost per pair) 32 bits
+    if (((int64_t)max_ctx_len + 8 + 64) * 8 * view->n_kv_local >= ((int64_t)1 << 31))
+        return KV_ERR_UNSUPPORTED;
     const int n_waves = streamk_waves();
     const size_t need_sk = kv_streamk_workspace_bytes(view, batch, n_waves);
     if (!workspace) return KV_ERR_INVALID_ARG;

@@ -246,6 +246,11 @@ def test_strerror_and_options():
         with pytest.raises(kv.KVError):
             kv.kv_set_option("xcd_skew", bad)
     kv.kv_set_option("xcd_skew", -1)
+    assert kv.kv_get_option("piece_cost") == -1
+    kv.kv_set_option("piece_cost", 64)
+    with pytest.raises(kv.KVError):
+        kv.kv_set_option("piece_cost", 65)
+    kv.kv_set_option("piece_cost", -1)
     kv.kv_set_option("linear_splits", 16)
     with pytest.raises(kv.KVError):
         kv.kv_set_option("linear_splits", 17)

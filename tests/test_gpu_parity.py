@@ -162,6 +162,26 @@ def test_long_sequences_cut_over_every_wavefront_head_groups():
     check_close(got, want, "long sequence, head groups")
 
 
+@pytest.mark.parametrize("cost", [0, 8, 64])
+def test_cost_of_a_pair_start_in_the_cut(cost):
+    """The cut over the wavefronts counts the start of every (sequence, head group) pair as `cost`
+    eighths of a tile; 64 (eight tiles) is the largest the option allows.  Many short sequences
+    (the cost dominates the weighted axis, many wavefronts get ranges that start exactly at a pair),
+    a mix, and a few long ones; four heads and one head per wavefront."""
+    kv.kv_set_option("piece_cost", cost)
+    try:
+        for lens in (list(range(1, 120)), [1, 31, 32, 33, 0, 511, 513, 4100, 2049, 64, 7000, 96], [20000, 0, 12345]):
+            lens = np.array(lens, dtype=np.int32)
+            for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 8, 5)]:
+                w = wl.Workload("cost", 74, 32, 8, 128, 16, len(lens), "x", ())
+                c = make_case(w, triple, lens)
+                want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
+                got = run_gpu_decode(c, gpu_view(w, triple))
+                check_close(got, want, f"cost {cost} {triple} {len(lens)} sequences")
+    finally:
+        kv.kv_set_option("piece_cost", -1)
+
+
 @pytest.mark.parametrize("skew", [0, 100, 256])
 def test_uneven_shares_between_xcds(skew):
     """The split gives wavefronts on even- and odd-numbered XCDs ranges of different length; 256 is
