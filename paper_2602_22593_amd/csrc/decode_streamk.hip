@@ -320,12 +320,12 @@ __device__ __forceinline__ bool split_prologue(const kv_streamk_args& a, int pai
         int lo = 0;
         {
             const int probe = lane * chunk;
-            const bool ok = probe < a.batch && wpos_lane(probe) <= u;
+            const bool ok = probe < a.batch && wpos_lane(min(probe, a.batch)) <= u;
             lo = (__builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)) - 1) * chunk;   // lane 0 always counts
         }
         if (chunk > 1) {
             const int probe = lo + lane;
-            const bool ok = lane < chunk && probe < a.batch && wpos_lane(probe) <= u;
+            const bool ok = lane < chunk && probe < a.batch && wpos_lane(min(probe, a.batch)) <= u;
             lo += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)) - 1;
         }
         t.s = lo;
