@@ -221,7 +221,17 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                                                                             sacc[b][h], 0, 0, 0);
                 }
             // ---- online softmax per column ------------------------------------------------------------
-            const bool masked = base + 31 > min_pos;
+            // the causal mask, only on the tiles that reach past some query of this wavefront (one
+            // uniform branch around all of it: most tiles lie wholly before every query)
+            if (base + 31 > min_pos) {
+#pragma unroll
+                for (int b = 0; b < R; ++b)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            sacc[b][h][i] = (base + 16 * h + 4 * i + quad <= pos[b]) ? sacc[b][h][i] : kNegInf;
+            }
             bf16x8 pb[R];
 #pragma unroll
             for (int b = 0; b < R; ++b) {
@@ -234,11 +244,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float x = sacc[b][h][i];
-                        if (masked) x = (base + 16 * h + 4 * i + quad <= pos[b]) ? x : kNegInf;
-                        sv[4 * h + i] = x;
-                    }
+                    for (int i = 0; i < 4; ++i) sv[4 * h + i] = sacc[b][h][i];
                 float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
                 // m[b] is the same in the four lanes of a column, so each lane can test its own eight
