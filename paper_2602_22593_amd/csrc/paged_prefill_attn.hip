@@ -34,6 +34,7 @@ constexpr int D = 128;
 constexpr int kThreads = 256;
 constexpr int kSub = 2;               // 32-key sub-tiles per staged tile
 constexpr int kKeys = 32 * kSub;      // keys per staged tile (one barrier each)
+constexpr float kUnset = 1e30f;       // exponent addend of a column that has no reference maximum yet
 
 struct prefill_args {
     const uint16_t* q;      // [total_q][n_q_local][128]
@@ -171,11 +172,13 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     };
 
     float m[R];
+    float neg_mc[R];  // -m scale log2(e), the addend of the exponent; kUnset while m = -inf
     f32x4 l[R];     // sum of the weights of the column, the same in all four entries and lanes of it
     f32x4 o[R][8];  // o[b][j][i] = O[column][16 j + 4 quad + i]
 #pragma unroll
     for (int b = 0; b < R; ++b) {
         m[b] = kNegInf;
+        neg_mc[b] = kUnset;
         l[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -198,7 +201,6 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 
     const int k_row = 4 * (r & 3) + (r >> 2);
     constexpr float kLag = 8.0f;
-    const float lag_raw = kLag / a.scale_log2e;
     auto compute = [&](int buf, int tile) {
 #pragma unroll
       for (int sub = 0; sub < kSub; ++sub) {
@@ -235,35 +237,47 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             bf16x8 pb[R];
 #pragma unroll
             for (int b = 0; b < R; ++b) {
-                // Scores stay in the products' own units; the scale is folded into the exponent.
-                // m[b] is a reference maximum that is allowed to lag behind the true running
-                // maximum by up to kLag in the exponent: weights then reach 2^kLag at most (exact in
-                // fp32 and in the bf16 operand alike), and the accumulators are rescaled only when
-                // some column's maximum has moved further than that -- rarely, after the first tiles.
-                float sv[8];
+                // Scores stay in the products' own units; the scale is folded into the exponent:
+                // t = (score - m) scale log2(e), weight = 2^t.  m[b] is a reference maximum that is
+                // allowed to lag behind the true running maximum by up to kLag in the exponent:
+                // weights then reach 2^kLag at most (exact in fp32 and in the bf16 operand alike), and
+                // the accumulators are rescaled only when some column's maximum has moved further than
+                // that -- rarely, after the first tiles.  m[b] is the same in the four lanes of a
+                // column, so each lane tests its own eight exponents and the maximum crosses lanes only
+                // on the rare tile that moves it.  While a column has seen no valid key (m = -inf; with
+                // the key range split it may never see one) its addend is kUnset: any finite score then
+                // gives a huge exponent and forces the first move, a masked one stays at -inf.
+                float t[8];
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) sv[4 * h + i] = sacc[b][h][i];
-                float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                                 fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-                // m[b] is the same in the four lanes of a column, so each lane can test its own eight
-                // scores against it: the maximum has to cross lanes only on the rare tile that moves it
-                // (with the key range split, a column may have seen no valid key yet: m = -inf)
-                if (__builtin_amdgcn_ballot_w64(mx > m[b] + lag_raw) != 0) {
+                    for (int i = 0; i < 4; ++i)
+                        t[4 * h + i] = __builtin_fmaf(sacc[b][h][i], a.scale_log2e, neg_mc[b]);
+                const float tmax = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
+                                         fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+                if (__builtin_amdgcn_ballot_w64(tmax > kLag) != 0) {
+                    float mx = fmaxf(fmaxf(fmaxf(sacc[b][0][0], sacc[b][0][1]), fmaxf(sacc[b][0][2], sacc[b][0][3])),
+                                     fmaxf(fmaxf(sacc[b][1][0], sacc[b][1][1]), fmaxf(sacc[b][1][2], sacc[b][1][3])));
                     mx = fmaxf(mx, __shfl_xor(mx, 16));
                     mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m[b], mx);
-                    const float alpha = fast_exp2((m[b] - m_new) * a.scale_log2e);
-                    l[b] *= alpha;
+                    if (m_new != kNegInf) {
+                        const float alpha = fast_exp2((m[b] - m_new) * a.scale_log2e);   // 0 on the first move
+                        l[b] *= alpha;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) o[b][j] *= alpha;
-                    m[b] = m_new;
+                        for (int j = 0; j < 8; ++j) o[b][j] *= alpha;
+                        m[b] = m_new;
+                        neg_mc[b] = -m_new * a.scale_log2e;
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            t[4 * h + i] = __builtin_fmaf(sacc[b][h][i], a.scale_log2e, neg_mc[b]);
                 }
-                const float neg_mc = (m[b] == kNegInf) ? 0.f : -m[b] * a.scale_log2e;
                 float p[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) p[u] = fast_exp2(__builtin_fmaf(sv[u], a.scale_log2e, neg_mc));
+                for (int u = 0; u < 8; ++u) p[u] = fast_exp2(t[u]);
                 pb[b] = as_bf16x8(kv_u32x4{pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
                                            pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])});
             }
