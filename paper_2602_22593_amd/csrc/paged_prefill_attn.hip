@@ -99,34 +99,6 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const int t_begin = split * per_split;
     const int n_tiles = min(all_tiles, t_begin + per_split);
 
-    // ---- this lane's query rows (B operands), one per row block --------------------------------
-    bf16x8 qb[R][4];
-    int pos[R];       // position of the column's query token
-    int64_t orow[R];  // element offset of the column's output row, or -1 if the column is padding
-#pragma unroll
-    for (int b = 0; b < R; ++b) {
-        const int rho = (wave * R + b) * 16 + r;
-        // a token takes 2^group_shift rows of the tile, the first G of which are its query heads
-        const int jt = j0 + (rho >> a.group_shift), g = rho & ((1 << a.group_shift) - 1);
-        const int jc = min(jt, q_len - 1);
-        pos[b] = first_pos + jc;
-        const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + min(g, G - 1)) * D;
-        orow[b] = (jt < q_len && g < G) ? row : -1;
-        const char* qrow = reinterpret_cast<const char*>(a.q + row) + quad * 16;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            qb[b][kk] = as_bf16x8(*reinterpret_cast<const kv_u32x4*>(qrow + kk * 64));
-    }
-    // keys below this position need no mask for any column of the wavefront
-    int min_pos = pos[0];
-#pragma unroll
-    for (int b = 1; b < R; ++b) min_pos = min(min_pos, pos[b]);
-#pragma unroll
-    for (int off = 1; off < 16; off <<= 1) min_pos = min(min_pos, __shfl_xor(min_pos, off));
-    min_pos = uniform(min_pos);
-    int max_pos = pos[R - 1];
-    max_pos = uniform(__shfl(max_pos, 15));  // rows ascend with the column: the last is the largest
-
     // ---- staging: lane tau fetches piece tau % 16 of rows tau / 16 and 16 + tau / 16 of a tile --
     const int ld_row = tid >> 4, ld_c = tid & 15;
     const int token_stride_bytes = v.token_stride * 2;
@@ -136,30 +108,51 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const int last_half = (n - 1) >> 4;
     typedef const __attribute__((address_space(4))) int32_t* const_ids;
     const const_ids ids = (const_ids)(a.table + (int64_t)s * a.table_stride);
-    const char* head_base = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D) + ld_c * 16;
+    const char* pool_head = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D);
+    const int64_t block_bytes = (int64_t)v.block_elems * 2;
+    // this lane's piece within a group of 16 consecutive token rows of one block
+    const uint32_t lane_off = (uint32_t)(ld_row * token_stride_bytes + ld_c * 16);
 
-    // address of this lane's piece of key row (tile, half h): rows past the end of the sequence
-    // are replaced by its last token (finite data, masked later)
-    auto piece = [&](int tile, int h) -> const char* {
-        const int hh = min(2 * kSub * tile + h, last_half);
-        const int hb = half_shift >= 0 ? (hh >> half_shift) : hh / halves_per_block;
-        const int blk = ids[hb];
-        const int tok = min(kKeys * tile + 16 * h + ld_row, n - 1);
-        const int slot = tok - hb * v.block_tokens;
-        return head_base + (int64_t)blk * (v.block_elems * 2) + (int64_t)slot * token_stride_bytes;
-    };
     // Two register stages: tile t's pieces travel in stage t % 2, are issued two tiles ahead of
     // their use and written to LDS one tile ahead, so a whole tile's arithmetic lies between a load
     // and the first wait for it.  Tiles past the last are replaced by the last (loads stay
     // unconditional, so every wait leaves exactly the younger stage in flight).
     kv_u32x4 stage_k[2][2 * kSub], stage_v[2][2 * kSub];
     auto fetch = [&](int stg, int tile) {
+        // the four groups of 16 rows of the tile (a group lies in one block); groups past the end of
+        // the sequence are replaced by its last group, rows past the end by its last token (finite
+        // data, masked later)
+        int hh[2 * kSub], hb[2 * kSub], blk[2 * kSub];
 #pragma unroll
-        for (int h = 0; h < 2 * kSub; ++h) {
-            const char* p = piece(tile, h);
-            // ordinary (cached) loads: every query tile of the sequence reads these keys again
-            stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(p);
-            stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(p + plane_bytes);
+        for (int h = 0; h < 2 * kSub; ++h) hh[h] = min(2 * kSub * tile + h, last_half);
+        if (half_shift >= 0) {
+#pragma unroll
+            for (int h = 0; h < 2 * kSub; ++h) hb[h] = hh[h] >> half_shift;
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2 * kSub; ++h) hb[h] = hh[h] / halves_per_block;
+        }
+#pragma unroll
+        for (int h = 0; h < 2 * kSub; ++h) blk[h] = ids[hb[h]];
+        // ordinary (cached) loads: every query tile of the sequence reads these keys again
+        if (2 * kSub * tile + 2 * kSub - 1 < last_half) {
+            // every row of the tile exists: one scalar base per group, the lane's offset is fixed
+#pragma unroll
+            for (int h = 0; h < 2 * kSub; ++h) {
+                const char* base = pool_head + blk[h] * block_bytes +
+                                   (int64_t)(16 * hh[h] - hb[h] * v.block_tokens) * token_stride_bytes;
+                stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(base + lane_off);
+                stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(base + plane_bytes + lane_off);
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2 * kSub; ++h) {
+                const int tok = min(16 * hh[h] + ld_row, n - 1);
+                const int slot = tok - hb[h] * v.block_tokens;
+                const char* p = pool_head + ld_c * 16 + blk[h] * block_bytes + (int64_t)slot * token_stride_bytes;
+                stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(p);
+                stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(p + plane_bytes);
+            }
         }
     };
     auto stash = [&](int stg, int buf) {
@@ -192,8 +185,41 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const bf16x8 ones = as_bf16x8(kv_u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 
     const int last_tile = n_tiles - 1;
+    if (t_begin < n_tiles) fetch(0, t_begin);
+    // ---- this lane's query rows (B operands), one per row block --------------------------------
+    bf16x8 qb[R][4];
+    int pos[R];       // position of the column's query token
+    int64_t orow[R];  // element offset of the column's output row, or -1 if the column is padding
+#pragma unroll
+    for (int b = 0; b < R; ++b) {
+        const int rho = (wave * R + b) * 16 + r;
+        // a token takes 2^group_shift rows of the tile, the first G of which are its query heads
+        const int jt = j0 + (rho >> a.group_shift), g = rho & ((1 << a.group_shift) - 1);
+        const int jc = min(jt, q_len - 1);
+        pos[b] = first_pos + jc;
+        const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + min(g, G - 1)) * D;
+        orow[b] = (jt < q_len && g < G) ? row : -1;
+        const char* qrow = reinterpret_cast<const char*>(a.q + row) + quad * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qb[b][kk] = as_bf16x8(*reinterpret_cast<const kv_u32x4*>(qrow + kk * 64));
+    }
+    // keys below this position need no mask for any column of the wavefront
+    int min_pos = pos[0];
+#pragma unroll
+    for (int b = 1; b < R; ++b) min_pos = min(min_pos, pos[b]);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) min_pos = min(min_pos, __shfl_xor(min_pos, off));
+    min_pos = uniform(min_pos);
+    int max_pos = pos[R - 1];
+    max_pos = uniform(__shfl(max_pos, 15));  // rows ascend with the column: the last is the largest
+
+    // Everything issued so far (the first tile, then the query rows) is waited for here, on every
+    // path, with an explicit vmcnt(0).  Left to the compiler's own bookkeeping, the query-row loads
+    // stay "possibly in flight" at the head of the loop below, and it then waits for the oldest staged
+    // tile before the first products of every tile instead of after the last.
+    __builtin_amdgcn_s_waitcnt(0x0f70);
     if (t_begin < n_tiles) {
-        fetch(0, t_begin);
         stash(0, 0);
         __syncthreads();
         fetch(1, min(t_begin + 1, last_tile));
@@ -304,9 +330,10 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         compute(0, tile);
         stash(1, 1);
         __syncthreads();
-        if (tile + 1 >= n_tiles) break;
+        // no early exit after an odd number of tiles: a second way out of the loop makes the compiler
+        // wait for the staged loads at the top of every round
         fetch(1, min(tile + 3, last_tile));
-        compute(1, tile + 1);
+        if (tile + 1 < n_tiles) compute(1, tile + 1);
         stash(0, 0);
         __syncthreads();
     }
