@@ -238,6 +238,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
             f32x4 sacc[R][2];
 #pragma unroll
             for (int b = 0; b < R; ++b) sacc[b][0] = sacc[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -249,6 +250,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                                                                             sacc[b][h], 0, 0, 0);
                 }
             // ---- online softmax per column ------------------------------------------------------------
+            __builtin_amdgcn_s_setprio(0);
             // the causal mask, only on the tiles that reach past some query of this wavefront (one
             // uniform branch around all of it: most tiles lie wholly before every query)
             if (base + 31 > min_pos) {
@@ -308,6 +310,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                                            pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])});
             }
             // ---- O^T += V^T P^T --------------------------------------------------------------------------
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int b = 0; b < R; ++b) l[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[b], l[b], 0, 0, 0);
             const char* vt = reinterpret_cast<const char*>(sv) + vt_tok * 256 + (r & 1) * 8;
@@ -322,6 +325,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                 for (int b = 0; b < R; ++b)
                     o[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[b], o[b][j], 0, 0, 0);
             }
+            __builtin_amdgcn_s_setprio(0);
         }
       }
     };
