@@ -175,8 +175,19 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
     if (i >= quads) return;
     const int64_t m = i / (p.Nl / 4), n = (i - m * (p.Nl / 4)) * 4;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int z = 0; z < p.splits; ++z)
-        s += *reinterpret_cast<const f32x4*>(p.part + ((int64_t)z * p.M + m) * p.Nl + n);
+    // four partial tiles requested at a time, then added in order (one memory round trip per four
+    // splits instead of one per split)
+    const float* src = p.part + m * p.Nl + n;
+    const int64_t step = (int64_t)p.M * p.Nl;
+    for (int z0 = 0; z0 < p.splits; z0 += 4) {
+        f32x4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            v[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)min(z0 + j, p.splits - 1) * step);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (z0 + j < p.splits) s += v[j];
+    }
     uint2 pk;
     pk.x = pack_bf16x2(s[0], s[1]);
     pk.y = pack_bf16x2(s[2], s[3]);
