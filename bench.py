@@ -51,6 +51,71 @@ def cpu_baseline(case, target_seconds=10.0):
     }, ref
 
 
+def library_context(kv, wqkv, wo):
+    """What torch's own kernels (the vendor libraries behind them) do on this GPU for the same shapes:
+    causal SDPA on contiguous, un-paged K/V, and matmul on contiguous weights.  Each GEMM is timed
+    as a replayed HIP graph of one call per weight copy, and so is kv_linear_view beside it, so that
+    neither side pays per-call host time.  Context for the reader, not a target and not a parity check."""
+    import torch
+    import torch.nn.functional as F
+
+    def graph_us(calls):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                for c in calls:
+                    c()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for c in calls:
+                c()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (20 * len(calls)) * 1e3
+
+    out = {"sdpa_causal_contiguous": [], "matmul_graph": []}
+    for what, B, hq, hkv, S in (("8 prompts of 4096 tokens, 32 q / 8 kv heads", 8, 32, 8, 4096),
+                                ("8 prompts of 4096 tokens, 16 q / 4 kv heads", 8, 16, 4, 4096)):
+        q = torch.randn(B, hq, S, 128, device="cuda", dtype=torch.bfloat16)
+        k = torch.randn(B, hkv, S, 128, device="cuda", dtype=torch.bfloat16)
+        v = torch.randn(B, hkv, S, 128, device="cuda", dtype=torch.bfloat16)
+        fn = lambda: F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=True)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        flops = 4.0 * 128 * hq * B * (S * (S + 1) / 2)
+        out["sdpa_causal_contiguous"].append({"what": what, "ms": round(ms, 4), "TFLOPs": round(flops / ms / 1e9, 1)})
+        del q, k, v
+        torch.cuda.empty_cache()
+    hq, hkv, d, hidden, M = 32, 8, 128, 4096, 64
+    x = torch.randn((M, hidden), device="cuda").to(torch.bfloat16)
+    for name, ws, view in (("qkv", wqkv, kv.kv_weight_view_fused_qkv(hq, hkv, d, hidden, 0, 1)),
+                           ("wo", wo, kv.kv_weight_view_make(1, 0, 1, hidden, hq * d))):
+        ys = [torch.empty((M, w.shape[0]), dtype=torch.bfloat16, device="cuda") for w in ws]
+        lib_us = graph_us([(lambda w=w, y=y: torch.matmul(x, w.t(), out=y)) for w, y in zip(ws, ys)])
+        own_us = graph_us([(lambda w=w, y=y: kv.kv_linear_view(x, w, view, out=y)) for w, y in zip(ws, ys)])
+        out["matmul_graph"].append({"layer": name, "M": M, "tp_degree": 1, "torch_matmul_us": round(lib_us, 2),
+                                    "kv_linear_view_us": round(own_us, 2)})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +126,9 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="independent pools cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip repack and the other workloads")
+    ap.add_argument("--library-context", action="store_true",
+                    help="also time the vendor libraries through torch on the same shapes (context only): "
+                         "SDPA on contiguous K/V for the prefill cases, matmul on the weight slices")
     ap.add_argument("--probe", action="store_true",
                     help="only run the known-traffic streaming kernels (read 1 GiB, copy 1 GiB) and exit")
     args = ap.parse_args()
@@ -272,6 +340,8 @@ def main():
                                          "unit": "GB/s", "frac": round(wbytes / k_ms / 1e6 / HBM_PEAK_GBPS, 4)},
                             "TFLOPs": round(2.0 * M * view.n_rows * view.col_count / k_ms / 1e9, 1)})
         extras["kv_linear_view"] = lin
+        if args.library_context:
+            extras["library_context"] = library_context(kv, wqkv, wo)
         result["extras"] = extras
 
     print(json.dumps(result))
