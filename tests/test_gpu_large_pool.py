@@ -98,3 +98,19 @@ def test_every_entry_point_on_a_pool_past_4gib():
     torch.cuda.synchronize()
     ids, got = touched(t_dp)
     assert np.array_equal(got, pool[ids]), "DP blocks after the append"
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 1), (16, 4)])
+def test_one_million_token_sequence(hq, hkv):
+    """One sequence of 2^20 tokens next to a short one: tile counts, prefix sums and piece lists
+    eight times longer than the longest benchmark sequence (one head per wavefront, and four)."""
+    from helpers import make_case
+    w = wl.Workload("million", 62 + hkv, hq, hkv, 128, 16, 2, "x", ())
+    ctx = np.array([1 << 20, 100], dtype=np.int32)
+    c = make_case(w, (LAYOUT_DP, 1, 0), ctx, slack=1.01)
+    view = kv.kv_view_create(hq, hkv, 128, 16, LAYOUT_DP, 1, 0)
+    out = kv.paged_decode_attn(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                               torch.from_numpy(c.ctx).to(DEV), view, max_ctx_len=int(ctx.max()))
+    torch.cuda.synchronize()
+    check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)),
+                oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx), f"2^20 tokens, {hq}/{hkv} heads")
