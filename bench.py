@@ -181,7 +181,8 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     gbps = case.kv_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # --- per-kernel durations from HIP events on the launch stream (separate pass) -------------
+    # --- per-kernel durations from HIP events on the launch stream (separate pass): the kernels'
+    #     own start and end times, taken by the launch itself -----------------------------------------
     kv.kv_profile_enable(True)
     for i in range(args.steps):
         run(i)

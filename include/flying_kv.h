@@ -305,9 +305,13 @@ int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);
 
 /*
- * Measurement aid (not part of the method).  While enabled, paged_decode_attn and kv_repack
- * bracket each of their kernels with HIP events recorded on the caller's stream, so that a
- * benchmark can read per-kernel durations without an external profiler.
+ * Measurement aid (not part of the method).  While enabled, the entry points time their kernels
+ * with HIP events on the caller's stream, so that a benchmark can read per-kernel durations
+ * without an external profiler: the even-split decode kernels are launched with events that
+ * take the kernel's own start and end times (hipExtLaunchKernelGGL; what a profiler reports),
+ * the other kernels are bracketed by events recorded before and after the launch (which also
+ * counts the dispatch, 2-3 us; the two kernels of paged_prefill_attn and of kv_linear_view
+ * share one bracket).
  *   kv_profile_enable(on)  : 1 = start recording (drops earlier records), 0 = stop.
  *   kv_profile_read(which, &total_ms, &n) : synchronises on the recorded events, returns the
  *       summed duration and the number of launches of kernel `which` since enabling, and

@@ -24,6 +24,8 @@
 // 16 h + 4 i + quad: so A row r of half h is token 16 h + 4 (r % 4) + r / 4, V rows are loaded
 // as they lie in memory (lane (c = r, quad) reads bytes [16 c, 16 c + 16) of tokens 4 i' + quad)
 // and transposed inside the lane with byte permutes.  Only the running maximum crosses lanes.
+#include <hip/hip_ext.h>
+
 #include "decode_common.h"
 
 using namespace kvdec;
@@ -1003,32 +1005,35 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
         const int64_t pc = kv_option_piece_cost();
         a.piece_units = (int32_t)(pc < 0 ? kDefaultPieceUnits : pc);
     }
-    int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
+    // (while kv_profile is on, each kernel is launched with a pair of events that take its own start
+    // and end times)
+    auto launch = [&](auto kernel, const dim3& g, const dim3& b, int which) {
+        hipEvent_t e0, e1;
+        if (kv_prof_kernel_events(which, &e0, &e1)) hipExtLaunchKernelGGL(kernel, g, b, 0, st, e0, e1, 0, a);
+        else hipLaunchKernelGGL(kernel, g, b, 0, st, a);
+    };
     if (hpw == 4) {
-        if (a.view_ids) hipLaunchKernelGGL((decode_wide_kernel<4, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((decode_wide_kernel<4, false>), grid, block, 0, st, a);
+        if (a.view_ids) launch(decode_wide_kernel<4, true>, grid, block, KV_PROF_DECODE_MAIN);
+        else launch(decode_wide_kernel<4, false>, grid, block, KV_PROF_DECODE_MAIN);
     } else if (hpw == 2) {
-        if (a.view_ids) hipLaunchKernelGGL((decode_wide_kernel<2, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((decode_wide_kernel<2, false>), grid, block, 0, st, a);
+        if (a.view_ids) launch(decode_wide_kernel<2, true>, grid, block, KV_PROF_DECODE_MAIN);
+        else launch(decode_wide_kernel<2, false>, grid, block, KV_PROF_DECODE_MAIN);
     } else if (a.view_ids) {
-        hipLaunchKernelGGL((decode_streamk_kernel<1, 1, true>), grid, block, 0, st, a);
+        launch(decode_streamk_kernel<1, 1, true>, grid, block, KV_PROF_DECODE_MAIN);
     } else
     switch (kv_option_variant() & 3) {
-        case 0: hipLaunchKernelGGL((decode_streamk_kernel<1, 1, false>), grid, block, 0, st, a); break;
-        case 1: hipLaunchKernelGGL((decode_streamk_kernel<0, 1, false>), grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((decode_streamk_kernel<1, 0, false>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((decode_streamk_kernel<0, 0, false>), grid, block, 0, st, a); break;
+        case 0: launch(decode_streamk_kernel<1, 1, false>, grid, block, KV_PROF_DECODE_MAIN); break;
+        case 1: launch(decode_streamk_kernel<0, 1, false>, grid, block, KV_PROF_DECODE_MAIN); break;
+        case 2: launch(decode_streamk_kernel<1, 0, false>, grid, block, KV_PROF_DECODE_MAIN); break;
+        default: launch(decode_streamk_kernel<0, 0, false>, grid, block, KV_PROF_DECODE_MAIN); break;
     }
-    kv_prof_end(KV_PROF_DECODE_MAIN, slot, st);
     int rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn launch");
     if (rc) return rc;
-    slot = kv_prof_begin(KV_PROF_DECODE_MERGE, st);
     // kMergeLong or more pieces per pair on average: expect long lists, split their columns
     const bool few_pairs = (int64_t)a.batch * a.pairs * kMergeLong <= a.n_waves;
-    hipLaunchKernelGGL(decode_streamk_merge_kernel,
-                       dim3((unsigned)view->n_q_local, (unsigned)a.batch, few_pairs ? (unsigned)kMergeSplit : 1u),
-                       dim3(256), 0, st, a);
-    kv_prof_end(KV_PROF_DECODE_MERGE, slot, st);
+    launch(decode_streamk_merge_kernel,
+           dim3((unsigned)view->n_q_local, (unsigned)a.batch, few_pairs ? (unsigned)kMergeSplit : 1u), dim3(256),
+           KV_PROF_DECODE_MERGE);
     return kv_record_hip_error(hipGetLastError(), "paged_decode_attn merge launch");
 }

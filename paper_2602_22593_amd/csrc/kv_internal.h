@@ -90,6 +90,11 @@ int64_t kv_option_linear_splits();
 // Per-kernel event brackets for kv_profile_*: begin returns a slot (or -1 when disabled).
 int kv_prof_begin(int which, hipStream_t st);
 void kv_prof_end(int which, int slot, hipStream_t st);
+// The same record filled by the launch itself: while profiling is on, hands out the two events of the
+// next record, to be passed to hipExtLaunchKernelGGL, which stamps them with the kernel's own start
+// and end (what a profiler reports as the kernel's duration; an event recorded on the stream before
+// and after the launch also counts the dispatch).  False when profiling is off: launch normally.
+bool kv_prof_kernel_events(int which, hipEvent_t* start, hipEvent_t* stop);
 
 // ---- matrix-core decode kernel with an even split over resident wavefronts --------------------
 #define KV_STREAMK_MAX_BATCH 2048

@@ -69,6 +69,24 @@ void kv_prof_end(int which, int slot, hipStream_t st)
     (void)hipEventRecord(g_prof[which].end[slot], st);
 }
 
+bool kv_prof_kernel_events(int which, hipEvent_t* start, hipEvent_t* stop)
+{
+    if (!g_prof_on) return false;
+    prof_kind& k = g_prof[which];
+    if (k.used >= kProfMax) return false;
+    if (k.used == k.begin.size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return false;
+        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return false; }
+        k.begin.push_back(a);
+        k.end.push_back(b);
+    }
+    const size_t slot = k.used++;
+    *start = k.begin[slot];
+    *stop = k.end[slot];
+    return true;
+}
+
 extern "C" {
 
 int kv_profile_enable(int on)
