@@ -316,7 +316,8 @@ int64_t kv_get_option(const char* key);
  *   kv_profile_read(which, &total_ms, &n) : synchronises on the recorded events, returns the
  *       summed duration and the number of launches of kernel `which` since enabling, and
  *       clears them.  which: 0 = decode main kernel, 1 = decode merge kernel, 2 = repack kernel.
- * Not thread-safe; at most 4096 launches per kernel are kept between reads.
+ * Not thread-safe; at most 4096 launches per kernel are kept between reads.  Leave it off while a
+ * HIP graph is being captured on the stream (event records are not part of the method's work).
  */
 enum { KV_PROF_DECODE_MAIN = 0, KV_PROF_DECODE_MERGE = 1, KV_PROF_REPACK = 2, KV_PROF_PREFILL = 3,
        KV_PROF_LINEAR = 4, KV_PROF_KINDS = 5 };
