@@ -293,10 +293,10 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
  *                   one-head-per-wavefront kernel), bit 2 one KV head per wavefront even where
  *                   several adjacent heads per wavefront are possible
  *   "xcd_skew"      even-split decode kernels: share moved from each odd-numbered to each even-numbered
- *                   XCD, in 1/1024 of an even share (0..256; -1 = the library's default, 64)
+ *                   XCD, in 1/1024 of an even share (0..256; -1 = the library's default, 80)
  *   "piece_cost"    even-split decode kernels: what the start of a (sequence, head group) pair counts
  *                   for when the work is cut over the wavefronts, in eighths of a 16 KiB tile
- *                   (0..64; -1 = the library's default, 8)
+ *                   (0..64; -1 = the library's default: 8 with one KV head per wavefront, 16 with several)
  *   "linear_splits" workgroups sharing the input dimension of one output tile in kv_linear_view
  *                   (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
  *                   follows the option, so size the workspace after setting it

@@ -37,8 +37,11 @@ constexpr int kSkWaves = kSkThreads / 64;
 constexpr int kMaxBatch = KV_STREAMK_MAX_BATCH;
 constexpr int D = 128;
 constexpr int kMaxClasses = 8;
-constexpr int kDefaultXcdSkew = 64;
-constexpr int kDefaultPieceUnits = 8;   // start of a pair, in eighths of a tile
+constexpr int kDefaultXcdSkew = 80;
+// What a piece boundary counts for in the cut, in eighths of a tile (measured optimum: one tile
+// with one head per wavefront, two with several -- their partial tiles and query rows are larger)
+constexpr int kDefaultPieceUnits = 8;
+constexpr int kDefaultPieceUnitsWide = 16;
 
 struct tile_regs {
     kv_u32x4 k[2][4];  // [half][kk]
@@ -1003,7 +1006,7 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
         // total weight = n_waves * 1024 in both cases (the skews of a round of eight cancel)
         a.inv_weight = 1.0 / ((double)a.n_waves * 1024.0);
         const int64_t pc = kv_option_piece_cost();
-        a.piece_units = (int32_t)(pc < 0 ? kDefaultPieceUnits : pc);
+        a.piece_units = (int32_t)(pc < 0 ? (hpw > 1 ? kDefaultPieceUnitsWide : kDefaultPieceUnits) : pc);
     }
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
     // (while kv_profile is on, each kernel is launched with a pair of events that take its own start
