@@ -47,7 +47,8 @@ def cpu_baseline(case, target_seconds=10.0):
         "value": round(case.kv_bytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": threads,
         "kind": "oracle",
         "sample": f"all {len(ctx)} sequences of the workload, {reps} full passes, "
-                  f"{spent / reps:.2f} s per pass (fp64, OpenMP over (sequence, query head))",
+                  f"{spent / reps:.2f} s per pass, {spent * threads:.0f} core-seconds in all "
+                  f"(fp64, OpenMP over (sequence, query head))",
     }, ref
 
 
