@@ -21,6 +21,11 @@
  *     and Bv * Hrow = base_block_size * n_kv_heads for every view, so block_bytes
  *     = 2 * base_block_size * n_kv_heads * head_dim * 2 never changes (Eq. 2 held constant).
  *   - Token t of sequence s lives in block block_table[s][t / Bv], slot t % Bv.
+ *   - Calls may be issued from several host threads and on several streams at once as long as
+ *     calls that share a workspace (or write the same blocks or rows) are ordered by the caller,
+ *     on one stream or by events: the library keeps nothing between calls except the
+ *     process-wide options, the calling thread's last HIP error text and the measurement
+ *     records below.
  */
 #ifndef FLYING_KV_H
 #define FLYING_KV_H

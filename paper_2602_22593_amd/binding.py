@@ -163,11 +163,18 @@ def paged_decode_attn_workspace_bytes(view: KVView, batch: int, max_ctx_len: int
     return int(lib().paged_decode_attn_workspace_bytes(view.handle, batch, max_ctx_len))
 
 
-def _workspace(device, nbytes: int) -> torch.Tensor:
-    key = (device.type, device.index)
+def _workspace(device, nbytes: int, stream=None) -> torch.Tensor:
+    """Scratch for a call that was given none: one buffer per (device, stream), grown on demand.
+    Calls on one stream are ordered and may share it; calls on different streams get their own."""
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    key = (device.index, stream.cuda_stream)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        # used on `stream`, whichever stream was current when it was allocated: its memory must not be
+        # handed out again before that stream's work is done
+        ws.record_stream(stream)
         _workspaces[key] = ws
     return ws
 
@@ -192,7 +199,7 @@ def paged_decode_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch
     n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // view.block_bytes
     need = paged_decode_attn_workspace_bytes(view, batch, max_ctx_len)
     if workspace is None:
-        workspace = _workspace(q.device, need)
+        workspace = _workspace(q.device, need, stream)
     rc = lib().paged_decode_attn(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),
         n_pool_blocks, _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
@@ -222,7 +229,7 @@ def paged_decode_attn_mixed(q: torch.Tensor, kv_pool: torch.Tensor, block_table:
     n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // v0.block_bytes
     need = paged_decode_attn_workspace_bytes(v0, batch, max_ctx_len)
     if workspace is None:
-        workspace = _workspace(q.device, need)
+        workspace = _workspace(q.device, need, stream)
     handles = (C.c_void_p * len(views))(*[v.handle for v in views])
     rc = lib().paged_decode_attn_mixed(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),
@@ -257,7 +264,7 @@ def paged_prefill_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torc
     need = int(lib().paged_prefill_attn_workspace_bytes(view.handle, batch, total_q, int(max_ctx_len),
                                                         int(max_q_len)))
     if workspace is None:
-        workspace = _workspace(q.device, need)
+        workspace = _workspace(q.device, need, stream)
     rc = lib().paged_prefill_attn(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"), n_pool_blocks,
         _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
@@ -303,7 +310,7 @@ def kv_linear_view(x: torch.Tensor, w_full: torch.Tensor, view: kv_weight_view,
         out = torch.empty((M, view.n_rows), dtype=torch.bfloat16, device=x.device)
     need = int(lib().kv_linear_view_workspace_bytes(C.byref(view), M))
     if workspace is None:
-        workspace = _workspace(x.device, need)
+        workspace = _workspace(x.device, need, stream)
     rc = lib().kv_linear_view(_dev_rows(x, _BF16, "x"), x.stride(0), _dev_rows(w_full, _BF16, "w_full"),
                               int(w_full.shape[0]), w_full.stride(0), C.byref(view),
                               _dev_rows(out, _BF16, "out"), out.stride(0), M,
