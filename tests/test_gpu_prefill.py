@@ -112,3 +112,21 @@ def test_long_prompt_sampled_rows():
         rh = np.tile(np.arange(hql, dtype=np.int32), len(rows))
         want = oracle.paged_prefill_rows(c.view, c.q, c.pool, c.table, c.ctx, c.q_off, rq, rh)
         check_close(got[rq, rh], want, f"long {triple}")
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.3, 0.002])
+@pytest.mark.parametrize("triple", [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 4, 2)])
+def test_sharp_and_flat_softmax(triple, scale):
+    """scale 1.0 at d = 128 gives logits of +-30 and more: nearly one-hot weights, and the reference
+    maximum of the lazily rescaled accumulators moves many times along a row of tiles (also across
+    the split key ranges of the second sequence); 0.002 is nearly uniform.  Every row compared."""
+    w = wl.Workload("prefill_sharp", 88, 32, 8, 128, 16, 3, "x", ())
+    ctx, qlen = np.array([700, 5000, 65], dtype=np.int32), np.array([700, 40, 1], dtype=np.int32)
+    c = make_prefill_case(w, triple, ctx, qlen)
+    out = kv.paged_prefill_attn(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                                torch.from_numpy(c.ctx).to(DEV), torch.from_numpy(c.q_off.astype(np.int32)).to(DEV),
+                                gpu_view(w, triple), max_ctx_len=int(ctx.max()), max_q_len=int(qlen.max()), scale=scale)
+    torch.cuda.synchronize()
+    got = bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
+    want = oracle.paged_prefill(c.view, c.q, c.pool, c.table, c.ctx, c.q_off, scale)
+    check_close(got, want, f"scale {scale} {triple}")
