@@ -4,10 +4,11 @@
 //
 // A workgroup of four wavefronts owns, for one (sequence, local KV head), a tile of query rows:
 // 64 R rows = (64 R / G) consecutive new tokens x the G query heads that share the KV head; each
-// wavefront holds R blocks of 16 rows.  The workgroup walks the cached tokens in tiles of 32,
-// staging each K and V tile once in LDS (double buffered, fetched with 16-byte loads by all 256
-// lanes while the previous tile is being consumed); each wavefront then takes its MFMA operands
-// from LDS and re-uses every K / V operand for its R row blocks.
+// wavefront holds R blocks of 16 rows.  The workgroup walks the cached tokens in staged tiles of
+// 64 (two sub-tiles of 32), each K and V tile going once from global memory straight into LDS
+// (16 bytes per lane with the load-to-LDS instruction, no registers in between; double buffered:
+// the next tile lands while the current one is consumed); each wavefront then takes its MFMA
+// operands from LDS and re-uses every K / V operand for its R row blocks.
 //
 // Per tile and row block, lane l = (c = l % 16, quad = l / 16), exactly as in the decode kernel:
 //   S^T[token][c] = K[token][:] . q[c][:]     A operand = K rows from LDS (token 16 h + 4 (r % 4)
@@ -73,8 +74,10 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 {
     // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)); V pieces at
     // c ^ (2 * ((t / 4) % 4)), which puts the four rows a transposing read touches in different banks
-    __shared__ kv_u32x4 s_k[2][512 * kSub];
-    __shared__ kv_u32x4 s_v[2][512 * kSub];
+    // one array per buffer: the compiler then knows that the loads landing in one buffer do not touch
+    // the operands being read from the other
+    __shared__ kv_u32x4 s_k0[512 * kSub], s_k1[512 * kSub];
+    __shared__ kv_u32x4 s_v0[512 * kSub], s_v1[512 * kSub];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = uniform(tid >> 6);
@@ -99,8 +102,13 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const int t_begin = split * per_split;
     const int n_tiles = min(all_tiles, t_begin + per_split);
 
-    // ---- staging: lane tau fetches piece tau % 16 of rows tau / 16 and 16 + tau / 16 of a tile --
-    const int ld_row = tid >> 4, ld_c = tid & 15;
+    // ---- staging: K and V tiles go from global memory straight into LDS, 16 bytes per lane; one
+    // instruction of a wavefront fills 64 consecutive 16-byte slots = 4 rows of 16 pieces, and
+    // which piece of its row a lane fetches is the LDS swizzle applied on the global side.
+    // Instruction i of wavefront w fills rows 16 i + 4 w .. + 3 of the tile (group i of 16 rows lies
+    // in one block).
+    const int dma_r = lane >> 4, dma_c = lane & 15;
+    const int row16 = 4 * wave + dma_r;                       // row within its group of 16
     const int token_stride_bytes = v.token_stride * 2;
     const int64_t plane_bytes = v.plane_elems * 2;
     const int halves_per_block = v.block_tokens >> 4;
@@ -110,18 +118,15 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const const_ids ids = (const_ids)(a.table + (int64_t)s * a.table_stride);
     const char* pool_head = reinterpret_cast<const char*>(a.pool + v.head_off + hl * D);
     const int64_t block_bytes = (int64_t)v.block_elems * 2;
-    // this lane's piece within a group of 16 consecutive token rows of one block
-    const uint32_t lane_off = (uint32_t)(ld_row * token_stride_bytes + ld_c * 16);
-
-    // Two register stages: tile t's pieces travel in stage t % 2, are issued two tiles ahead of
-    // their use and written to LDS one tile ahead, so a whole tile's arithmetic lies between a load
-    // and the first wait for it.  Tiles past the last are replaced by the last (loads stay
-    // unconditional, so every wait leaves exactly the younger stage in flight).
-    kv_u32x4 stage_k[2][2 * kSub], stage_v[2][2 * kSub];
-    auto fetch = [&](int stg, int tile) {
-        // the four groups of 16 rows of the tile (a group lies in one block); groups past the end of
-        // the sequence are replaced by its last group, rows past the end by its last token (finite
-        // data, masked later)
+    const uint32_t k_piece = (uint32_t)((dma_c ^ row16) << 4);
+    const uint32_t v_piece = (uint32_t)((dma_c ^ (2 * wave)) << 4);   // 2 ((row / 4) % 4), row / 4 = 4 i + w
+    const uint32_t lane_off_k = (uint32_t)(row16 * token_stride_bytes) + k_piece;
+    const uint32_t lane_off_v = (uint32_t)(row16 * token_stride_bytes) + v_piece;
+    typedef const __attribute__((address_space(1))) void* global_ptr;
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int last_tile = n_tiles - 1;
+    // rows past the end of the sequence are replaced by its last token (finite data, masked later)
+    auto stage_tile = [&](int tile, kv_u32x4* dk, kv_u32x4* dv) {
         int hh[2 * kSub], hb[2 * kSub], blk[2 * kSub];
 #pragma unroll
         for (int h = 0; h < 2 * kSub; ++h) hh[h] = min(2 * kSub * tile + h, last_half);
@@ -136,32 +141,28 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
         for (int h = 0; h < 2 * kSub; ++h) blk[h] = ids[hb[h]];
         // ordinary (cached) loads: every query tile of the sequence reads these keys again
         if (2 * kSub * tile + 2 * kSub - 1 < last_half) {
-            // every row of the tile exists: one scalar base per group, the lane's offset is fixed
 #pragma unroll
             for (int h = 0; h < 2 * kSub; ++h) {
                 const char* base = pool_head + blk[h] * block_bytes +
                                    (int64_t)(16 * hh[h] - hb[h] * v.block_tokens) * token_stride_bytes;
-                stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(base + lane_off);
-                stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(base + plane_bytes + lane_off);
+                __builtin_amdgcn_global_load_lds((global_ptr)(base + lane_off_k), (lds_ptr)(dk + (4 * h + wave) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_ptr)(base + plane_bytes + lane_off_v), (lds_ptr)(dv + (4 * h + wave) * 64), 16, 0, 0);
             }
         } else {
 #pragma unroll
             for (int h = 0; h < 2 * kSub; ++h) {
-                const int tok = min(16 * hh[h] + ld_row, n - 1);
+                const int tok = min(16 * hh[h] + row16, n - 1);
                 const int slot = tok - hb[h] * v.block_tokens;
-                const char* p = pool_head + ld_c * 16 + blk[h] * block_bytes + (int64_t)slot * token_stride_bytes;
-                stage_k[stg][h] = *reinterpret_cast<const kv_u32x4*>(p);
-                stage_v[stg][h] = *reinterpret_cast<const kv_u32x4*>(p + plane_bytes);
+                const char* p = pool_head + blk[h] * block_bytes + (int64_t)slot * token_stride_bytes;
+                __builtin_amdgcn_global_load_lds((global_ptr)(p + k_piece), (lds_ptr)(dk + (4 * h + wave) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_ptr)(p + plane_bytes + v_piece), (lds_ptr)(dv + (4 * h + wave) * 64), 16, 0, 0);
             }
         }
     };
-    auto stash = [&](int stg, int buf) {
-#pragma unroll
-        for (int h = 0; h < 2 * kSub; ++h) {
-            const int row = 16 * h + ld_row;
-            s_k[buf][row * 16 + (ld_c ^ ld_row)] = stage_k[stg][h];
-            s_v[buf][row * 16 + (ld_c ^ (2 * ((row >> 2) & 3)))] = stage_v[stg][h];
-        }
+    // all of this wavefront's loads have landed in LDS; then every wavefront's
+    auto staged = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+        __syncthreads();
     };
 
     float m[R];
@@ -184,8 +185,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     const int vt_swz = 2 * ((vt_tok >> 2) & 3);   // the same for token 16 + vt_tok
     const bf16x8 ones = as_bf16x8(kv_u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 
-    const int last_tile = n_tiles - 1;
-    if (t_begin < n_tiles) fetch(0, t_begin);
+    if (t_begin < n_tiles) stage_tile(t_begin, s_k0, s_v0);
     // ---- this lane's query rows (B operands), one per row block --------------------------------
     bf16x8 qb[R][4];
     int pos[R];       // position of the column's query token
@@ -214,16 +214,7 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     int max_pos = pos[R - 1];
     max_pos = uniform(__shfl(max_pos, 15));  // rows ascend with the column: the last is the largest
 
-    // Everything issued so far (the first tile, then the query rows) is waited for here, on every
-    // path, with an explicit vmcnt(0).  Left to the compiler's own bookkeeping, the query-row loads
-    // stay "possibly in flight" at the head of the loop below, and it then waits for the oldest staged
-    // tile before the first products of every tile instead of after the last.
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    if (t_begin < n_tiles) {
-        stash(0, 0);
-        __syncthreads();
-        fetch(1, min(t_begin + 1, last_tile));
-    }
+    staged();
 
     const int k_row = 4 * (r & 3) + (r >> 2);
     constexpr float kLag = 8.0f;
@@ -231,8 +222,8 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 #pragma unroll
       for (int sub = 0; sub < kSub; ++sub) {
         const int base = kKeys * tile + 32 * sub;
-        const kv_u32x4* const sk = s_k[buf] + 512 * sub;
-        const kv_u32x4* const sv = s_v[buf] + 512 * sub;
+        const kv_u32x4* const sk = (buf ? s_k1 : s_k0) + 512 * sub;
+        const kv_u32x4* const sv = (buf ? s_v1 : s_v0) + 512 * sub;
         if (base <= max_pos) {  // else every key of the sub-tile lies after all of this wavefront's queries
             // ---- S^T = K q^T ------------------------------------------------------------------------
             f32x4 sacc[R][2];
@@ -330,16 +321,12 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
       }
     };
     for (int tile = t_begin; tile < n_tiles; tile += 2) {
-        fetch(0, min(tile + 2, last_tile));
+        stage_tile(min(tile + 1, last_tile), s_k1, s_v1);
         compute(0, tile);
-        stash(1, 1);
-        __syncthreads();
-        // no early exit after an odd number of tiles: a second way out of the loop makes the compiler
-        // wait for the staged loads at the top of every round
-        fetch(1, min(tile + 3, last_tile));
+        staged();
+        stage_tile(min(tile + 2, last_tile), s_k0, s_v0);
         if (tile + 1 < n_tiles) compute(1, tile + 1);
-        stash(0, 0);
-        __syncthreads();
+        staged();
     }
 
     // ---- normalise and store ------------------------------------------------------------------------
