@@ -5,7 +5,7 @@
 // A workgroup of four wavefronts owns, for one (sequence, local KV head), a tile of query rows:
 // 64 R rows = (64 R / G) consecutive new tokens x the G query heads that share the KV head; each
 // wavefront holds R blocks of 16 rows.  The workgroup walks the cached tokens in staged tiles of
-// 64 (two sub-tiles of 32), each K and V tile going once from global memory straight into LDS
+// 32, each K and V tile going once from global memory straight into LDS
 // (16 bytes per lane with the load-to-LDS instruction, no registers in between; double buffered:
 // the next tile lands while the current one is consumed); each wavefront then takes its MFMA
 // operands from LDS and re-uses every K / V operand for its R row blocks.
@@ -33,7 +33,7 @@ namespace {
 
 constexpr int D = 128;
 constexpr int kThreads = 256;
-constexpr int kSub = 2;               // 32-key sub-tiles per staged tile
+constexpr int kSub = 1;               // 32-key sub-tiles per staged tile
 constexpr int kKeys = 32 * kSub;      // keys per staged tile (one barrier each)
 constexpr float kUnset = 1e30f;       // exponent addend of a column that has no reference maximum yet
 
@@ -69,8 +69,11 @@ __device__ __forceinline__ bits16x4 lds_read_transposed(const void* p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_bits16x4_ptr)p);
 }
 
+// Three workgroups per compute unit (32 KiB of LDS and at most 168 registers each): with nothing staged
+// in registers the kernel fits, and a third wavefront per SIMD hides more of the chain K read -> scores ->
+// softmax -> V read -> output of the other two than the longer 64-key tiles of two workgroups did.
 template <int R>
-__global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefill_args a)
+__global__ __launch_bounds__(kThreads, R <= 2 ? 3 : 1) void prefill_kernel(prefill_args a)
 {
     // [buffer][row][piece]: K pieces swizzled (piece c of row t at c ^ (t % 16)); V pieces at
     // c ^ (2 * ((t / 4) % 4)), which puts the four rows a transposing read touches in different banks
@@ -189,16 +192,21 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
     // ---- this lane's query rows (B operands), one per row block --------------------------------
     bf16x8 qb[R][4];
     int pos[R];       // position of the column's query token
-    int64_t orow[R];  // element offset of the column's output row, or -1 if the column is padding
-#pragma unroll
-    for (int b = 0; b < R; ++b) {
+    // element offset of the row of column r of row block b in q and out, or -1 if the column is
+    // padding (recomputed at the end rather than kept in registers through the loop)
+    auto row_of = [&](int b, bool or_padding) -> int64_t {
         const int rho = (wave * R + b) * 16 + r;
         // a token takes 2^group_shift rows of the tile, the first G of which are its query heads
         const int jt = j0 + (rho >> a.group_shift), g = rho & ((1 << a.group_shift) - 1);
         const int jc = min(jt, q_len - 1);
-        pos[b] = first_pos + jc;
         const int64_t row = ((int64_t)(q0 + jc) * v.n_q_local + hl * G + min(g, G - 1)) * D;
-        orow[b] = (jt < q_len && g < G) ? row : -1;
+        return (or_padding || (jt < q_len && g < G)) ? row : -1;
+    };
+#pragma unroll
+    for (int b = 0; b < R; ++b) {
+        const int rho = (wave * R + b) * 16 + r;
+        pos[b] = first_pos + min(j0 + (rho >> a.group_shift), q_len - 1);
+        const int64_t row = row_of(b, true);
         const char* qrow = reinterpret_cast<const char*>(a.q + row) + quad * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -333,9 +341,10 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
 #pragma unroll
     for (int b = 0; b < R; ++b) {
         const float lt = l[b][0];
-        if (orow[b] >= 0 && a.splits > 1) {
+        const int64_t orow = row_of(b, false);
+        if (orow >= 0 && a.splits > 1) {
             // partial of this key range: row = index of the output row
-            const int64_t rec = (int64_t)split * a.rows + orow[b] / D;
+            const int64_t rec = (int64_t)split * a.rows + orow / D;
             float* dst = a.part_o + rec * D + 4 * quad;
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) *reinterpret_cast<f32x4*>(dst + 16 * jj) = o[b][jj];
@@ -343,9 +352,9 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 2 : 1) void prefill_kernel(prefi
                 a.part_ml[rec * 2 + 0] = m[b];
                 a.part_ml[rec * 2 + 1] = lt;
             }
-        } else if (orow[b] >= 0) {
+        } else if (orow >= 0) {
             const float inv = 1.0f / lt;
-            uint16_t* dst = a.out + orow[b] + 4 * quad;
+            uint16_t* dst = a.out + orow + 4 * quad;
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
                 uint2 pk;
@@ -389,7 +398,9 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(prefill_args a)
 constexpr int kRowBlocks = 2;  // 16-row blocks per wavefront (4 measured 2x slower: one wavefront per SIMD)
 
 // Workgroups sharing the key range of a query tile: only when the launch would otherwise leave
-// compute units idle (few sequences, few query tokens, long contexts); at least 16 key tiles each.
+// compute units idle (few sequences, few query tokens, long contexts): enough to fill the 768
+// workgroup slots of the chip (three per compute unit) once, measured better than one and a half
+// times; at least 512 keys each.
 int prefill_splits(const kv_view* view, int batch, int max_ctx_len, int max_q_len)
 {
     int shift = 0;
