@@ -1,4 +1,4 @@
-"""The decode step under HIP graph capture: the library allocates nothing and synchronises nothing in
+"""The entry points under HIP graph capture: the library allocates nothing and synchronises nothing in
 its hot path, so a serving loop can record append + attention once and replay it per token."""
 import numpy as np
 import pytest
@@ -50,3 +50,62 @@ def test_decode_call_replayed_from_a_graph(triple):
         got = bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
         err = np.abs(got - want)
         assert np.isfinite(got).all() and err.max() <= 2e-2 and err.mean() <= 2e-3, (rep, err.max(), err.mean())
+
+
+def test_prefill_and_projection_replayed_from_a_graph():
+    """One graph holding the QKV projection on a weight view and a multi-token attention call (with its
+    split-key-range merge kernel): replayed three times with fresh inputs copied into the captured
+    buffers, eager work in between; every replay against the oracle."""
+    from oracle import weights as ow
+    from helpers import make_prefill_case
+    w = wl.Workload("graph_prefill", 77, 32, 8, 128, 16, 2, "x", ())
+    ctx, qlen = np.array([6000, 900], dtype=np.int32), np.array([40, 33], dtype=np.int32)
+    c = make_prefill_case(w, (LAYOUT_TP, 2, 1), ctx, qlen)
+    view = kv.kv_view_create(32, 8, 128, 16, LAYOUT_TP, 2, 1)
+    q = dev_u16(c.q)
+    pool, table, n = dev_u16(c.pool), torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
+    q_off = torch.from_numpy(c.q_off.astype(np.int32)).to(DEV)
+    out = torch.zeros_like(q)
+    need = kv.lib().paged_prefill_attn_workspace_bytes(view.handle, 2, int(qlen.sum()), int(ctx.max()), int(qlen.max()))
+    assert need > 0                                   # the split path is the one captured
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    # the projection: 64 rows on rank 1's slice of a fused [6144][512] weight
+    hidden, M = 512, 64
+    gen = wl.generator(77, wl.SUB_MISC)
+    w_bits = wl.randn_bf16((6144, hidden), gen)
+    x_bits = wl.randn_bf16((M, hidden), gen)
+    wv = kv.kv_weight_view_fused_qkv(32, 8, 128, hidden, 1, 2)
+    ov = ow.weight_view_fused_qkv(32, 8, 128, hidden, 1, 2)
+    dw = torch.from_numpy(w_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    dx = torch.from_numpy(x_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    y = torch.zeros((M, wv.n_rows), dtype=torch.bfloat16, device=DEV)
+    lws = torch.empty(max(int(kv.lib().kv_linear_view_workspace_bytes(__import__("ctypes").byref(wv), M)), 256),
+                      dtype=torch.uint8, device=DEV)
+
+    def step():
+        kv.kv_linear_view(dx, dw, wv, out=y, workspace=lws)
+        kv.paged_prefill_attn(q, pool, table, n, q_off, view, int(ctx.max()), int(qlen.max()), out=out, workspace=ws)
+
+    step()                                            # eager warm-up
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        q_new = wl.randn_bf16(c.q.shape, gen)
+        x_new = wl.randn_bf16((M, hidden), gen)
+        q.copy_(dev_u16(q_new))
+        dx.copy_(torch.from_numpy(x_new.view(np.int16)).to(DEV).view(torch.bfloat16))
+        out.zero_()
+        y.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want = oracle.paged_prefill(c.view, q_new, c.pool, c.table, c.ctx, c.q_off)
+        got = bf16_bits_to_f64(out.cpu().numpy().view(np.uint16))
+        err = np.abs(got - want)
+        assert np.isfinite(got).all() and err.max() <= 2e-2 and err.mean() <= 2e-3, (rep, err.max(), err.mean())
+        want_y = ow.linear_view(x_new, w_bits, ov)
+        got_y = bf16_bits_to_f64(y.cpu().view(torch.int16).numpy().view(np.uint16))
+        tol = np.abs(want_y) * 2.0 ** -8 + 2.0 * hidden * hidden * 2.0 ** -24 + 1e-6
+        assert np.isfinite(got_y).all() and not (np.abs(got_y - want_y) > tol).any(), rep
