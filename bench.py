@@ -208,13 +208,13 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "us_per_layer": round(ms_per_step * 1e3, 2),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 K/V/q/out, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "view": {"layout": "DP" if triple[0] == 0 else "TP",
                                                 "tp_degree": triple[1], "rank": triple[2]},
                    "n_q_local": case.view.n_q_local, "n_kv_local": case.view.n_kv_local,
                    "head_dim": w.head_dim, "block_tokens": case.view.block_tokens,
                    "batch": w.batch, "tokens": int(case.ctx.sum()), "kv_bytes": case.kv_bytes,
-                   "pool_copies": args.copies,
+                   "pool_copies": args.copies, "storage": "bf16 K/V/q/out", "accumulate": "fp32",
                    "chunk_tokens": kv.kv_get_option("chunk_tokens")},
         "roofline": {"bound": "hbm", "kernel": "paged decode main kernel",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
