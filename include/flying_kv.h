@@ -163,6 +163,32 @@ int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * paged_decode_attn_static -- paged_decode_attn for callers that cannot allocate device memory or
+ * carry a workspace: code running under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, result and errors as paged_decode_attn, without the
+ * workspace: the scratch memory of the kernels is a fixed device array of
+ * KV_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until
+ * the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine); the first call on a device looks the array's address up once (hipGetSymbolAddress),
+ * so make that first call outside any stream capture.
+ *   KV_ERR_WORKSPACE   paged_decode_attn_workspace_bytes(view, batch, max_ctx_len) exceeds
+ *                      KV_STATIC_SCRATCH_BYTES (with the default options the array serves e.g. 1024
+ *                      sequences under the 8B-shaped DP view, 32 local query heads, and 2048 under
+ *                      its TP4 or TP8 rank views); nothing is launched
+ *   KV_ERR_UNSUPPORTED also for a device ordinal of 64 or more
+ * All calls on one GPU share that GPU's array: calls that may overlap there (different streams
+ * without an ordering between them, several host threads) race on it and give undefined results;
+ * order them on one stream or by events.  The array keeps the previous call's contents; nothing
+ * in it needs clearing, since every word the kernels read in a call is written earlier in that
+ * call.  (The measurement aid kv_profile_enable creates events while it is on; leave it off.)
+ */
+#define KV_STATIC_SCRATCH_BYTES (32u << 20)
+int paged_decode_attn_static(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
+                             const int32_t* block_table, int64_t block_table_stride,
+                             const int32_t* ctx_lens, int batch, int max_ctx_len,
+                             const kv_view* view, float scale, void* hip_stream);
+
+/*
  * paged_prefill_attn -- causal attention from several new tokens per sequence to everything
  * cached up to each of them, through a view: one chunk of a prefill (Sec. 2.1; chunked prefill
  * is kept, Sec. 3) or the recompute step of Soft Preempt (Sec. 5.2.2).  The new tokens' K and V

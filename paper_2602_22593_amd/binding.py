@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
     L.paged_decode_attn_workspace_bytes.restype = C.c_size_t
     L.paged_decode_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp, C.c_float,
                                     vp, C.c_size_t, vp]
+    L.paged_decode_attn_static.argtypes = [vp, vp, vp, i64, vp, i64, vp, C.c_int, C.c_int, vp, C.c_float, vp]
     L.paged_decode_attn_mixed.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, C.c_int, vp, C.c_int,
                                           C.c_float, vp, C.c_size_t, vp]
     L.paged_prefill_attn.argtypes = [vp, vp, vp, i64, vp, i64, vp, vp, C.c_int, i64, C.c_int, C.c_int, vp,
@@ -207,6 +208,26 @@ def paged_decode_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch
         float(scale), _dev(workspace, (torch.uint8,), "workspace"),
         workspace.numel(), _stream_ptr(stream))
     _check(rc, "paged_decode_attn")
+    return out
+
+
+def paged_decode_attn_static(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch.Tensor,
+                             ctx_lens: torch.Tensor, view: KVView, max_ctx_len: int,
+                             out: torch.Tensor, scale: float = 0.0, stream=None) -> torch.Tensor:
+    """paged_decode_attn on the library's own fixed scratch array: no workspace argument and no
+    allocation anywhere in the call (``out`` must be given)."""
+    batch = int(ctx_lens.shape[0])
+    if tuple(q.shape) != (batch, view.n_q_local, view.head_dim) or tuple(out.shape) != tuple(q.shape):
+        raise ValueError(f"q and out must have shape {(batch, view.n_q_local, view.head_dim)}")
+    if block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError("block_table must be [batch][max_blocks]")
+    n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // view.block_bytes
+    rc = lib().paged_decode_attn_static(
+        _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),
+        n_pool_blocks, _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
+        _dev(ctx_lens, (torch.int32,), "ctx_lens"), batch, int(max_ctx_len), view.handle,
+        float(scale), _stream_ptr(stream))
+    _check(rc, "paged_decode_attn_static")
     return out
 
 

@@ -16,6 +16,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "kv_internal.h"
 
 namespace {
@@ -660,6 +662,57 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
         rc = kv_record_hip_error(hipGetLastError(), "paged_decode_attn merge launch");
     }
     return rc;
+}
+
+// ---- paged_decode_attn for callers that cannot allocate ------------------------------------------
+// The scratch memory of the decode kernels (partial results of the pieces, pair descriptors) lives in
+// a file-scope device array instead of a caller's workspace.  Every GPU holds its own copy of the
+// array at its own address: in host code the array's name is only a handle for
+// hipGetSymbolAddress, which is asked once per device, with that device current; the pointer it
+// returns is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[KV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, null until asked
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return kv_record_hip_error(e, "paged_decode_attn_static: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return KV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return kv_record_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol,
+                                       "paged_decode_attn_static: hipGetSymbolAddress");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return KV_OK;
+}
+}  // namespace
+
+extern "C" int paged_decode_attn_static(const void* q, void* out, const void* kv_pool,
+                                        int64_t n_pool_blocks, const int32_t* block_table,
+                                        int64_t block_table_stride, const int32_t* ctx_lens, int batch,
+                                        int max_ctx_len, const kv_view* view, float scale,
+                                        void* hip_stream)
+{
+    if (!kv_view_ok(view) || batch < 0 || max_ctx_len < 0) return KV_ERR_INVALID_ARG;
+    if (batch == 0) return KV_OK;
+    if (paged_decode_attn_workspace_bytes(view, batch, max_ctx_len) > (size_t)KV_STATIC_SCRATCH_BYTES)
+        return KV_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc) return rc;
+    return paged_decode_attn(q, out, kv_pool, n_pool_blocks, block_table, block_table_stride, ctx_lens,
+                             batch, max_ctx_len, view, scale, ws, (size_t)KV_STATIC_SCRATCH_BYTES,
+                             hip_stream);
 }
 
 
