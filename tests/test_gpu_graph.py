@@ -9,7 +9,7 @@ from oracle import LAYOUT_DP, LAYOUT_TP
 from paper_2602_22593_amd import binding as kv
 from paper_2602_22593_amd import workloads as wl
 
-from helpers import bf16_bits_to_f64, make_case
+from helpers import bf16_bits_to_f64, linear_tolerance, make_case
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -107,5 +107,5 @@ def test_prefill_and_projection_replayed_from_a_graph():
         assert np.isfinite(got).all() and err.max() <= 2e-2 and err.mean() <= 2e-3, (rep, err.max(), err.mean())
         want_y = ow.linear_view(x_new, w_bits, ov)
         got_y = bf16_bits_to_f64(y.cpu().view(torch.int16).numpy().view(np.uint16))
-        tol = np.abs(want_y) * 2.0 ** -8 + 2.0 * hidden * hidden * 2.0 ** -24 + 1e-6
+        tol = linear_tolerance(x_new, w_bits, ov, want_y)
         assert np.isfinite(got_y).all() and not (np.abs(got_y - want_y) > tol).any(), rep

@@ -9,7 +9,7 @@ from oracle import weights as ow
 from paper_2602_22593_amd import binding as kv
 from paper_2602_22593_amd import workloads as wl
 
-from helpers import bf16_bits_to_f64
+from helpers import bf16_bits_to_f64, linear_tolerance
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -23,15 +23,14 @@ def dev(a):
     return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
 
 
-def check(got_bits, want, K, what):
-    """fp32 accumulation of K products of N(0,1) values, one rounding to bf16 at the end: the
-    result differs from the fp64 value by at most half a bf16 ulp of it (2^-9 relative) plus the
-    accumulation error, K * 2^-24 * sum |x w| <~ K * 2^-24 * K; allow 2^-8 relative and that
-    absolute term (doubled)."""
+def check(got_bits, x, w, ov, what):
+    """Every output against the fp64 product, within the bound of helpers.linear_tolerance (half a
+    bf16 ulp of the result plus a sqrt(K)-scaled fp32 accumulation term on the exact sum of
+    |x w|)."""
+    want = ow.linear_view(x, w, ov)
     got = bf16_bits_to_f64(got_bits)
     assert np.isfinite(got).all(), what
-    tol = np.abs(want) * 2.0 ** -8 + 2.0 * K * K * 2.0 ** -24 + 1e-6
-    bad = np.abs(got - want) > tol
+    bad = np.abs(got - want) > linear_tolerance(x, w, ov, want)
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, worst {np.abs(got - want).max():.4g}"
 
 
@@ -56,7 +55,7 @@ def test_fused_qkv_column_slice(M, m, r):
     assert [(gv.row_start[i], gv.row_count[i]) for i in range(3)] == list(ov.row_segments)
     y = kv.kv_linear_view(dev(x), dev(w), gv)
     torch.cuda.synchronize()
-    check(y.cpu().view(torch.int16).numpy().view(np.uint16), ow.linear_view(x, w, ov), hidden, f"qkv M={M} {r}/{m}")
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), x, w, ov, f"qkv M={M} {r}/{m}")
 
 
 @pytest.mark.parametrize("M", [3, 64, 130])
@@ -74,8 +73,8 @@ def test_output_projection_row_slice(M, m, r):
     x_slice = dev(a_full)[:, ov.col_start:ov.col_start + ov.col_count]
     y = kv.kv_linear_view(x_slice, dev(w), gv)
     torch.cuda.synchronize()
-    want = ow.linear_view(np.ascontiguousarray(a_full[:, ov.col_start:ov.col_start + ov.col_count]), w, ov)
-    check(y.cpu().view(torch.int16).numpy().view(np.uint16), want, ov.col_count, f"wo M={M} {r}/{m}")
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16),
+          np.ascontiguousarray(a_full[:, ov.col_start:ov.col_start + ov.col_count]), w, ov, f"wo M={M} {r}/{m}")
 
 
 def test_output_rows_outside_the_batch_are_untouched():
@@ -86,7 +85,7 @@ def test_output_rows_outside_the_batch_are_untouched():
     torch.cuda.synchronize()
     assert (out[M:] == 7.0).all() and (out[:, hidden:] == 7.0).all()
     check(out[:M, :hidden].contiguous().cpu().view(torch.int16).numpy().view(np.uint16),
-          ow.linear_view(x, w, ow.weight_view(0, 0, 1, hidden, kin)), kin, "padded out")
+          x, w, ow.weight_view(0, 0, 1, hidden, kin), "padded out")
 
 
 @pytest.mark.parametrize("splits", [0, 1, 2, 3, 5, 16])
@@ -106,4 +105,4 @@ def test_every_cut_of_the_input_dimension(slabs, splits):
         torch.cuda.synchronize()
     finally:
         kv.kv_set_option("linear_splits", 0)
-    check(y.cpu().view(torch.int16).numpy().view(np.uint16), ow.linear_view(x, w, ov), K, f"slabs {slabs} splits {splits}")
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), x, w, ov, f"slabs {slabs} splits {splits}")

@@ -13,7 +13,7 @@ import oracle
 from paper_2602_22593_amd import binding as kv
 from paper_2602_22593_amd import workloads as wl
 
-from helpers import bf16_bits_to_f64, make_case, make_prefill_case
+from helpers import bf16_bits_to_f64, linear_tolerance, make_case, make_prefill_case
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -223,10 +223,9 @@ def test_random_linear_views(seed):
             y = kv.kv_linear_view(dx, dw, gv)
             torch.cuda.synchronize()
             got = bf16_bits_to_f64(y.cpu().view(torch.int16).numpy().view(np.uint16))
-            want = ow.linear_view(np.ascontiguousarray(xw[:, :ov.col_count]), np.ascontiguousarray(w[:, :n_cols]), ov)
-            kk = ov.col_count
-            # fp32 accumulation of kk products, one rounding to bf16 (as in the linear-view tests)
-            tol = np.abs(want) * 2.0 ** -8 + 2.0 * kk * kk * 2.0 ** -24 + 1e-6
+            xs, wsl = np.ascontiguousarray(xw[:, :ov.col_count]), np.ascontiguousarray(w[:, :n_cols])
+            want = ow.linear_view(xs, wsl, ov)
+            tol = linear_tolerance(xs, wsl, ov, want)
             assert np.isfinite(got).all() and not (np.abs(got - want) > tol).any(), what
     finally:
         kv.kv_set_option("linear_splits", 0)
