@@ -4,14 +4,15 @@
  * The library implements the device side of the paper's KV Cache Adaptor (Sec. 4.2): one
  * physical pool of constant-size KV blocks that is read either as a DP replica's blocks
  * (all KV heads, B_base tokens per block) or as one TP rank's blocks (H/p heads,
- * p * B_base tokens per block), the attention kernel being told "the stride and capacity
- * for the specific request" (Sec. 4.2.3).  On top of that contract it provides the decode
+ * p * B_base tokens per block); the kernels receive each request's token stride and block
+ * capacity (Sec. 4.2.3).  On top of that contract it provides the decode
  * attention kernel, a block repack kernel for the transitions where bytes must move (the
  * paper recomputes the cache there, Sec. 5.2.2), and the KV append kernel.
  *
  * Conventions
  *   - Every function returns 0 (KV_OK) or a negative kv_status.  Nothing throws, nothing
- *     synchronises the stream, nothing allocates device memory.
+ *     synchronises the stream, nothing allocates device memory (kv_validate_tables, a
+ *     debugging aid, is the one exception to the first two).
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary host memory.  The library owns only kv_view objects (host).
  *   - bf16 everywhere in memory; all accumulation is fp32 on the device.
@@ -117,8 +118,13 @@ int kv_view_strides(const kv_view* view, int32_t* token_stride_elems, int32_t* r
  *                a smaller one makes the result undefined)
  *   scale        softmax scale; <= 0 selects 1 / sqrt(head_dim)
  *   workspace    device scratch of at least paged_decode_attn_workspace_bytes(view, batch,
- *                max_ctx_len) bytes, 256-byte aligned; contents need not be initialised
- *                and are undefined afterwards
+ *                max_ctx_len) bytes, 256-byte aligned.  Its first KV_DECODE_SYNC_BYTES hold the
+ *                arrival words through which the wavefronts that share a long sequence find
+ *                out which of them finishes it: they must be ZERO when the workspace is first
+ *                used (one hipMemsetAsync after allocating it) and every call leaves them zero
+ *                again, so one workspace serves any sequence of calls, of any shapes and views.
+ *                The rest need not be initialised; all of it is undefined while a call runs.
+ *                A workspace whose first bytes are not zero gives undefined output rows.
  *   hip_stream   hipStream_t to launch on (null = default stream)
  *
  * Block ids inside [0, n_pool_blocks) for every valid token are a precondition (not
@@ -127,6 +133,7 @@ int kv_view_strides(const kv_view* view, int32_t* token_stride_elems, int32_t* r
  * for max_ctx_len), KV_ERR_UNSUPPORTED (head_dim or group size without a kernel),
  * KV_ERR_WORKSPACE, KV_ERR_HIP.
  */
+#define KV_DECODE_SYNC_BYTES (16384 * 8)
 size_t paged_decode_attn_workspace_bytes(const kv_view* view, int batch, int max_ctx_len);
 int paged_decode_attn(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
                       const int32_t* block_table, int64_t block_table_stride,
@@ -178,9 +185,11 @@ int paged_decode_attn_mixed(const void* q, void* out, const void* kv_pool, int64
  *   KV_ERR_UNSUPPORTED also for a device ordinal of 64 or more
  * All calls on one GPU share that GPU's array: calls that may overlap there (different streams
  * without an ordering between them, several host threads) race on it and give undefined results;
- * order them on one stream or by events.  The array keeps the previous call's contents; nothing
- * in it needs clearing, since every word the kernels read in a call is written earlier in that
- * call.  (The measurement aid kv_profile_enable creates events while it is on; leave it off.)
+ * order them on one stream or by events.  The array keeps the previous call's contents: its
+ * arrival words start out zero (the array is zero when the library is loaded) and every call puts
+ * them back to zero; every other word a call reads is written earlier in that call, so nothing
+ * needs clearing between calls.  (The measurement aid kv_profile_enable creates events while it
+ * is on; leave it off.)
  */
 #define KV_STATIC_SCRATCH_BYTES (32u << 20)
 int paged_decode_attn_static(const void* q, void* out, const void* kv_pool, int64_t n_pool_blocks,
@@ -314,23 +323,27 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
                        const kv_view* other_view, const int32_t* other_table,
                        int64_t other_stride, void* hip_stream);
 
-/* Tunables for experiments and tests (process-wide; 0 = automatic unless stated otherwise):
- *   "chunk_tokens"  split-KV granularity of the chunked decode kernels, a multiple of 64
- *   "force_kernel"  decode kernel: 1 even split over resident wavefronts, 2 vector ALU, 3 chunked
- *                   matrix-core (KV_ERR_UNSUPPORTED from the call if the shape is not served)
- *   "waves_per_cu"  wavefronts per compute unit launched by the even-split kernel, a multiple of 4
- *   "variant"       build variant of the even-split kernel: bit 0 K operands fetched directly
- *                   instead of through LDS, bit 1 no register double buffering (both for the
- *                   one-head-per-wavefront kernel), bit 2 one KV head per wavefront even where
- *                   several adjacent heads per wavefront are possible
- *   "xcd_skew"      even-split decode kernels: share moved from each odd-numbered to each even-numbered
- *                   XCD, in 1/1024 of an even share (0..256; -1 = the library's default, 80)
- *   "piece_cost"    even-split decode kernels: what the start of a (sequence, head group) pair counts
- *                   for when the work is cut over the wavefronts, in eighths of a 16 KiB tile
- *                   (0..64; -1 = the library's default: 8 with one KV head per wavefront, 16 with several)
- *   "linear_splits" workgroups sharing the input dimension of one output tile in kv_linear_view
- *                   (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
- *                   follows the option, so size the workspace after setting it
+/* Test and tuning hooks.  Process-wide and NOT synchronised with calls in flight: set them from one
+ * thread while no other thread is inside the library, e.g. before serving starts or inside a test.
+ * A call reads each option once, when it is issued (a captured HIP graph keeps what it was
+ * captured with).  0 = automatic unless stated otherwise.
+ *   "chunk_tokens"   split-KV granularity of the chunked decode kernels, a multiple of 64
+ *   "force_kernel"   decode kernel: 1 even split over resident wavefronts, 2 vector ALU, 3 chunked
+ *                    matrix-core (KV_ERR_UNSUPPORTED from the call if the shape is not served)
+ *   "waves_per_cu"   wavefronts per compute unit launched by the even-split kernel, a multiple of 4.
+ *                    paged_decode_attn_workspace_bytes follows "force_kernel", "waves_per_cu" and
+ *                    "chunk_tokens": size the workspace after setting them
+ *   "heads_per_wave" 1: one KV head per wavefront even where several adjacent heads are possible
+ *   "merge_mode"     how the pieces of a sequence cut over several wavefronts are combined:
+ *                    1 inside the main kernel by the last piece to arrive, 2 by a second launch
+ *   "xcd_skew"       even-split decode kernels: share moved from each odd-numbered to each even-numbered
+ *                    XCD, in 1/1024 of an even share (0..256; -1 = the library's default)
+ *   "piece_cost"     even-split decode kernels: what the start of a (sequence, head group) pair counts
+ *                    for when the work is cut over the wavefronts, in eighths of a 16 KiB tile
+ *                    (0..64; -1 = the library's default, 16)
+ *   "linear_splits"  workgroups sharing the input dimension of one output tile in kv_linear_view
+ *                    (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
+ *                    follows the option, so size the workspace after setting it
  * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
 int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);

@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_PKG, "libflyingkv.so")
 KV_LAYOUT_DP = 0
 KV_LAYOUT_TP = 1
 
+KV_DECODE_SYNC_BYTES = 16384 * 8    # leading bytes of a decode workspace that must start out zero
+
 KV_OK, KV_ERR_INVALID_ARG, KV_ERR_UNSUPPORTED, KV_ERR_WORKSPACE, KV_ERR_HIP, KV_ERR_RANGE, KV_ERR_ALIAS = \
     0, -1, -2, -3, -4, -5, -6
 
@@ -164,18 +166,19 @@ def paged_decode_attn_workspace_bytes(view: KVView, batch: int, max_ctx_len: int
     return int(lib().paged_decode_attn_workspace_bytes(view.handle, batch, max_ctx_len))
 
 
-def _workspace(device, nbytes: int, stream=None) -> torch.Tensor:
-    """Scratch for a call that was given none: one buffer per (device, stream), grown on demand.
-    Calls on one stream are ordered and may share it; calls on different streams get their own."""
+def _workspace(device, nbytes: int, stream=None, kind: str = "scratch") -> torch.Tensor:
+    """Scratch for a call that was given none: one buffer per (device, stream, kind), grown on demand.
+    Calls on one stream are ordered and may share it; calls on different streams get their own.
+    Decode calls (kind "decode") keep a buffer to themselves: its leading arrival words must stay
+    zero between calls, and the other entry points write their scratch from the first byte on."""
     if stream is None:
         stream = torch.cuda.current_stream(device)
-    key = (device.index, stream.cuda_stream)
+    key = (device.index, stream.cuda_stream, kind)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
-        # used on `stream`, whichever stream was current when it was allocated: its memory must not be
-        # handed out again before that stream's work is done
-        ws.record_stream(stream)
+        # zero-filled: the decode kernels expect their arrival words (the first bytes) to start at zero
+        with torch.cuda.stream(stream):
+            ws = torch.zeros(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
         _workspaces[key] = ws
     return ws
 
@@ -200,7 +203,7 @@ def paged_decode_attn(q: torch.Tensor, kv_pool: torch.Tensor, block_table: torch
     n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // view.block_bytes
     need = paged_decode_attn_workspace_bytes(view, batch, max_ctx_len)
     if workspace is None:
-        workspace = _workspace(q.device, need, stream)
+        workspace = _workspace(q.device, need, stream, "decode")
     rc = lib().paged_decode_attn(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),
         n_pool_blocks, _dev(block_table, (torch.int32,), "block_table"), block_table.stride(0),
@@ -250,7 +253,7 @@ def paged_decode_attn_mixed(q: torch.Tensor, kv_pool: torch.Tensor, block_table:
     n_pool_blocks = kv_pool.numel() * kv_pool.element_size() // v0.block_bytes
     need = paged_decode_attn_workspace_bytes(v0, batch, max_ctx_len)
     if workspace is None:
-        workspace = _workspace(q.device, need, stream)
+        workspace = _workspace(q.device, need, stream, "decode")
     handles = (C.c_void_p * len(views))(*[v.handle for v in views])
     rc = lib().paged_decode_attn_mixed(
         _dev(q, _BF16, "q"), _dev(out, _BF16, "out"), _dev(kv_pool, _BF16, "kv_pool"),

@@ -82,7 +82,8 @@ int kv_record_hip_error(hipError_t e, const char* what);
 int64_t kv_option_chunk_tokens();
 int64_t kv_option_force_kernel();
 int64_t kv_option_waves_per_cu();
-int64_t kv_option_variant();
+int64_t kv_option_heads_per_wave();  // 0: as many adjacent KV heads per wavefront as the shape allows; 1: always one
+int64_t kv_option_merge_mode();      // 0: automatic; 1: pieces combined inside the main kernel; 2: by a second launch
 int64_t kv_option_piece_cost();  // -1: library default; else 0..64 eighths of a tile
 int64_t kv_option_xcd_skew();  // -1: library default; else 0..256 in 1/1024 of an even share
 int64_t kv_option_linear_splits();
@@ -116,9 +117,15 @@ struct kv_streamk_args {
     int32_t group;     // query heads per KV head
     int32_t batch;
     int32_t n_waves;   // wavefronts launched (multiple of 4)
-    float* part_acc;   // [n_waves + batch * n_kv_local][group][128]
-    float* part_ml;    // [n_waves + batch * n_kv_local][group][2]
+    float* part_acc;   // [n_waves + batch * pairs][cols][128]
+    float* part_ml;    // [n_waves + batch * pairs][cols][2]
     int32_t* pair_desc;   // [batch * pairs][2] numbers of the wavefronts holding a pair's first and last piece
+                          // (read by the merge kernel; unused when the main kernel combines the pieces)
+    unsigned long long* pair_sync;  // [batch * pairs] arrival words of the pairs, zero between calls
+    int32_t fused;        // 1: the last piece of a pair to arrive combines them all (no merge kernel)
+#ifdef KV_DECODE_TRACE
+    unsigned long long* trace;   // [n_waves][8] timestamps, development builds only
+#endif
     const int32_t* view_ids;  // [batch] index into lay[] per sequence, or null: every sequence under v
     int32_t n_views;
     kv_layout_dev lay[KV_MAX_MIXED_VIEWS];
@@ -133,5 +140,8 @@ struct kv_streamk_args {
     double inv_weight;       // 1 / (summed weight of all wavefronts)
     int32_t piece_units;     // weight of the start of a pair on the axis that is cut, a tile weighing 8
 };
+// Bytes at the start of every decode workspace that hold the arrival words: zero before the first
+// call on a workspace, and zero again when a call has finished.
+#define KV_DECODE_SYNC_WORDS (KV_DECODE_SYNC_BYTES / 8)
 size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves);
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st);

@@ -22,7 +22,8 @@ int kv_record_hip_error(hipError_t e, const char* what)
 static std::atomic<int64_t> g_chunk_tokens{0};
 static std::atomic<int64_t> g_force_kernel{0};
 static std::atomic<int64_t> g_waves_per_cu{0};
-static std::atomic<int64_t> g_variant{0};
+static std::atomic<int64_t> g_heads_per_wave{0};
+static std::atomic<int64_t> g_merge_mode{0};
 static std::atomic<int64_t> g_xcd_skew{-1};
 static std::atomic<int64_t> g_piece_cost{-1};
 static std::atomic<int64_t> g_linear_splits{0};
@@ -30,7 +31,8 @@ static std::atomic<int64_t> g_linear_splits{0};
 int64_t kv_option_chunk_tokens() { return g_chunk_tokens.load(); }
 int64_t kv_option_force_kernel() { return g_force_kernel.load(); }
 int64_t kv_option_waves_per_cu() { return g_waves_per_cu.load(); }
-int64_t kv_option_variant() { return g_variant.load(); }
+int64_t kv_option_heads_per_wave() { return g_heads_per_wave.load(); }
+int64_t kv_option_merge_mode() { return g_merge_mode.load(); }
 int64_t kv_option_xcd_skew() { return g_xcd_skew.load(); }
 int64_t kv_option_piece_cost() { return g_piece_cost.load(); }
 int64_t kv_option_linear_splits() { return g_linear_splits.load(); }
@@ -200,9 +202,14 @@ int kv_set_option(const char* key, int64_t value)
         g_force_kernel.store(value);
         return KV_OK;
     }
-    if (!strcmp(key, "variant")) {
-        if (value < 0 || value > 255) return KV_ERR_INVALID_ARG;
-        g_variant.store(value);
+    if (!strcmp(key, "heads_per_wave")) {
+        if (value < 0 || value > 1) return KV_ERR_INVALID_ARG;
+        g_heads_per_wave.store(value);
+        return KV_OK;
+    }
+    if (!strcmp(key, "merge_mode")) {
+        if (value < 0 || value > 2) return KV_ERR_INVALID_ARG;
+        g_merge_mode.store(value);
         return KV_OK;
     }
     if (!strcmp(key, "linear_splits")) {
@@ -234,7 +241,8 @@ int64_t kv_get_option(const char* key)
     if (!strcmp(key, "chunk_tokens")) return g_chunk_tokens.load();
     if (!strcmp(key, "force_kernel")) return g_force_kernel.load();
     if (!strcmp(key, "waves_per_cu")) return g_waves_per_cu.load();
-    if (!strcmp(key, "variant")) return g_variant.load();
+    if (!strcmp(key, "heads_per_wave")) return g_heads_per_wave.load();
+    if (!strcmp(key, "merge_mode")) return g_merge_mode.load();
     if (!strcmp(key, "xcd_skew")) return g_xcd_skew.load();
     if (!strcmp(key, "piece_cost")) return g_piece_cost.load();
     if (!strcmp(key, "linear_splits")) return g_linear_splits.load();

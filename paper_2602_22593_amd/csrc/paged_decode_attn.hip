@@ -16,39 +16,17 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
-#include "kv_internal.h"
+#include "decode_common.h"
+
+using namespace kvdec;
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr float kNegInf = -INFINITY;
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
-// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)f32_to_bf16_bits(f); }
-
-__device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8])
-{
-    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x);
-    f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
-    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z);
-    f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
-}
 
 struct decode_args {
     const uint16_t* q;
@@ -65,20 +43,6 @@ struct decode_args {
     float* part_acc;  // [batch][n_q_local][max_chunks][D]
     float* part_ml;   // [batch][n_q_local][max_chunks][2]
 };
-
-// Combine (m2, l2, a2[]) into (m, l, a[]); all maxima may be -inf (empty partials).
-template <int N>
-__device__ __forceinline__ void combine(float& m, float& l, float (&a)[N], float m2, float l2,
-                                        const float (&a2)[N])
-{
-    const float mn = fmaxf(m, m2);
-    const float ms = (mn == kNegInf) ? 0.f : mn;
-    const float c1 = exp2f(m - ms), c2 = exp2f(m2 - ms);
-    l = l * c1 + l2 * c2;
-#pragma unroll
-    for (int e = 0; e < N; ++e) a[e] = a[e] * c1 + a2[e] * c2;
-    m = mn;
-}
 
 // Workgroup epilogue shared by both main kernels: the kWaves per-wave results for G heads sit in
 // LDS (s_acc[w][g][e], s_ml[w][g][0..1]); combine them and write either the final bf16 row (the
@@ -131,8 +95,6 @@ __device__ __forceinline__ void finish_chunk(const decode_args& a, float (&s_acc
 // 4 i' + quad, i' = 0..7) and transposed inside the lane with byte permutes.  No data crosses
 // lanes except the running maximum.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8 as_bf16x8(kv_u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
-
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(decode_args a)
 {
     constexpr int D = 128;
@@ -509,29 +471,33 @@ int pick_kernel(const kv_view* view, int batch)
 }
 
 // Wavefronts the even-split kernel launches: all resident at once, one per SIMD by default
-// (fewer, fatter streams measured faster than more, thinner ones).
+// (fewer, fatter streams measured faster than more, thinner ones).  The compute-unit count is that
+// of the device current on the calling thread, asked once per device.
 int streamk_waves()
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    constexpr int kDevices = 64;
+    static std::atomic<int> cus[kDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) dev = 0;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
-        cus = n;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
     int64_t per_cu = kv_option_waves_per_cu();
     if (per_cu <= 0) per_cu = 4;
-    return (int)(cus * per_cu);
+    return (int)(n * per_cu);
 }
 
 size_t chunked_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
 {
     const int chunk = pick_chunk_tokens(view, batch, max_ctx_len);
     const int64_t max_chunks = ((int64_t)max_ctx_len + chunk - 1) / chunk;
-    if (max_chunks <= 1) return 256;
+    if (max_chunks <= 1) return KV_DECODE_SYNC_BYTES + 256;
     const int64_t recs = (int64_t)batch * view->n_q_local * max_chunks;
-    return align_up((size_t)recs * view->geom.head_dim * 4, 256) + align_up((size_t)recs * 2 * 4, 256);
+    return KV_DECODE_SYNC_BYTES + align_up((size_t)recs * view->geom.head_dim * 4, 256) +
+           align_up((size_t)recs * 2 * 4, 256);
 }
 
 // The even-split matrix-core kernel.  views/view_ids non-null: sequence s is laid out as
@@ -581,7 +547,7 @@ static int launch_streamk(const void* q, void* out, const void* kv_pool, const i
 
 extern "C" size_t paged_decode_attn_workspace_bytes(const kv_view* view, int batch, int max_ctx_len)
 {
-    if (!kv_view_ok(view) || batch <= 0 || max_ctx_len <= 0) return 256;
+    if (!kv_view_ok(view) || batch <= 0 || max_ctx_len <= 0) return KV_DECODE_SYNC_BYTES + 256;
     const int kernel = pick_kernel(view, batch);
     if (kernel == 1) return kv_streamk_workspace_bytes(view, batch, streamk_waves());
     return chunked_workspace_bytes(view, batch, max_ctx_len);
@@ -635,10 +601,10 @@ extern "C" int paged_decode_attn(const void* q, void* out, const void* kv_pool,
     a.chunk_tokens = chunk;
     a.max_chunks = (int32_t)max_chunks;
     const int64_t recs = (int64_t)batch * view->n_q_local * max_chunks;
-    a.part_acc = (float*)workspace;
-    a.part_ml = max_chunks > 1
-                    ? (float*)((char*)workspace + align_up((size_t)recs * D * 4, 256))
-                    : nullptr;
+    // (the chunked kernels keep off the arrival words at the start of the workspace)
+    char* ws_base = workspace ? (char*)workspace + KV_DECODE_SYNC_BYTES : nullptr;
+    a.part_acc = (float*)ws_base;
+    a.part_ml = max_chunks > 1 ? (float*)(ws_base + align_up((size_t)recs * D * 4, 256)) : nullptr;
 
     const dim3 grid((unsigned)max_chunks, (unsigned)view->n_kv_local, (unsigned)batch);
     int slot = kv_prof_begin(KV_PROF_DECODE_MAIN, st);

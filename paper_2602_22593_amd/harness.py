@@ -96,7 +96,7 @@ def build_decode_case(w: wl.Workload, triple, device="cuda:0", n_copies: int = 1
                                  wl.SEED_BASE + 10 * w.index + wl.SUB_DATA + 1000 * (k + 1), device))
     max_ctx = int(ctx.max())
     ws_bytes = kv.paged_decode_attn_workspace_bytes(view, len(ctx), max_ctx)
-    workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=device)
+    workspace = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=device)
     kv_bytes = int(ctx.astype(np.int64).sum()) * view.n_kv_local * view.head_dim * 2 * 2
     return DecodeCase(w, tuple(triple), view, ctx, max_ctx, tables, q, pools, tables_dev,
                       torch.from_numpy(ctx).to(device),
@@ -141,7 +141,7 @@ def build_mixed_case(w: wl.Workload, p: int, r: int, device="cuda:0", slack: flo
     lo = r * views[0].n_q_local
     q = torch.from_numpy(np.ascontiguousarray(q_full[:, lo:lo + views[0].n_q_local]).view(np.int16)) \
         .to(device).view(torch.bfloat16)
-    ws = torch.empty(max(kv.paged_decode_attn_workspace_bytes(views[0], len(ctx), int(ctx.max())), 256),
+    ws = torch.zeros(max(kv.paged_decode_attn_workspace_bytes(views[0], len(ctx), int(ctx.max())), 256),
                      dtype=torch.uint8, device=device)
     kv_bytes = int(ctx.astype(np.int64).sum()) * views[0].n_kv_local * views[0].head_dim * 2 * 2
     return MixedCase(views, ctx, q, torch.empty_like(q), pool, torch.from_numpy(table).to(device),

@@ -31,7 +31,7 @@ def test_decode_call_replayed_from_a_graph(triple):
     q = dev_u16(c.q)
     pool, table, n = dev_u16(c.pool), torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
     out = torch.zeros_like(q)
-    ws = torch.empty(kv.paged_decode_attn_workspace_bytes(view, len(lens), int(lens.max())), dtype=torch.uint8, device=DEV)
+    ws = torch.zeros(kv.paged_decode_attn_workspace_bytes(view, len(lens), int(lens.max())), dtype=torch.uint8, device=DEV)
     kv.paged_decode_attn(q, pool, table, n, view, int(lens.max()), out=out, workspace=ws)   # eager warm-up
     torch.cuda.synchronize()
 

@@ -24,8 +24,8 @@ def require_gpu_and_library():
     assert torch.cuda.is_available(), "these tests need a GPU"
     kv.lib()  # raises if the HIP library is not built: there is no fallback
     yield
-    kv.kv_set_option("chunk_tokens", 0)
-    kv.kv_set_option("force_kernel", 0)
+    for key in ("chunk_tokens", "force_kernel", "heads_per_wave", "merge_mode", "waves_per_cu"):
+        kv.kv_set_option(key, 0)
 
 
 def dev_u16(a: np.ndarray) -> torch.Tensor:
@@ -93,14 +93,29 @@ def test_multi_tile_ragged_lengths(hq, hkv, triple, chunk, kernel):
         assert np.array_equal(got[0, i], bf16_bits_to_f64(c.V[c.seq_off[0], g]))
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
+def poisoned_workspace(nbytes: int, fill: int) -> torch.Tensor:
+    """A workspace full of garbage except for what the ABI asks to be zero at first use: the arrival
+    words in its first KV_DECODE_SYNC_BYTES."""
+    ws = torch.full((nbytes,), fill, dtype=torch.uint8, device=DEV)
+    ws[:kv.KV_DECODE_SYNC_BYTES] = 0
+    return ws
+
+
+def sync_words_are_zero(ws: torch.Tensor) -> bool:
+    torch.cuda.synchronize()
+    return not bool(ws[:kv.KV_DECODE_SYNC_BYTES].any())
+
+
+@pytest.mark.parametrize("merge_mode", [0, 1, 2])
+@pytest.mark.parametrize("one_head", [0, 1])
 @pytest.mark.parametrize("wpc", [4, 12])
-def test_even_split_kernel_variants(variant, wpc):
-    """The even-split matrix-core kernel in its build variants (several adjacent KV heads per
-    wavefront where the shape allows, or always one: bit 2; for one head, K fetched operand-wise or
-    row-wise through LDS, with or without register double buffering) and launch widths; lengths
-    chosen so that wavefront ranges cross sequence and head boundaries and single-piece pairs occur."""
-    kv.kv_set_option("variant", variant)
+def test_even_split_kernel_variants(one_head, merge_mode, wpc):
+    """The even-split matrix-core kernels in their modes (several adjacent KV heads per wavefront
+    where the shape allows, or always one; cut sequences finished inside the main kernel or by the
+    merge kernel) and launch widths; lengths chosen so that wavefront ranges cross sequence and head
+    boundaries and single-piece pairs occur."""
+    kv.kv_set_option("heads_per_wave", one_head)
+    kv.kv_set_option("merge_mode", merge_mode)
     kv.kv_set_option("waves_per_cu", wpc)
     try:
         lens = np.array([1, 31, 32, 33, 0, 511, 513, 4100, 2049, 64, 7000, 96], dtype=np.int32)
@@ -110,10 +125,11 @@ def test_even_split_kernel_variants(variant, wpc):
             c = make_case(w, triple, lens)
             want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
             got = run_gpu_decode(c, gpu_view(w, triple))
-            check_close(got, want, f"variant {variant} wpc {wpc} {hq}/{hkv} {triple}")
+            check_close(got, want, f"one_head {one_head} merge {merge_mode} wpc {wpc} {hq}/{hkv} {triple}")
             assert (got[4] == 0).all()
     finally:
-        kv.kv_set_option("variant", 0)
+        kv.kv_set_option("heads_per_wave", 0)
+        kv.kv_set_option("merge_mode", 0)
         kv.kv_set_option("waves_per_cu", 0)
 
 
@@ -131,35 +147,41 @@ def test_several_heads_per_wavefront_every_tail_length(hq, hkv, triple):
     """The kernel that gives a wavefront 2 or 4 adjacent KV heads: every context length from 0 to
     40 (every fill of the last 8- or 16-token tile, with and without full tiles before it), plus
     lengths around block and window boundaries; the pool is NaN-poisoned outside the valid tokens.
-    Same shapes with one head per wavefront (variant bit 2) as the cross-check of the option."""
+    Same shapes with one head per wavefront as the cross-check of the option."""
     lens = np.array(list(range(41)) + [127, 128, 129, 1023, 1025, 2050], dtype=np.int32)
     w = wl.Workload("wide", 80 + hq // 8, hq, hkv, 128, 16, len(lens), "x", ())
     c = make_case(w, triple, lens)
     want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
     try:
-        for variant in (0, 4):
-            kv.kv_set_option("variant", variant)
+        for one_head in (0, 1):
+            kv.kv_set_option("heads_per_wave", one_head)
             got = run_gpu_decode(c, gpu_view(w, triple))
-            check_close(got, want, f"{hq}/{hkv} {triple} variant {variant}")
+            check_close(got, want, f"{hq}/{hkv} {triple} one_head {one_head}")
             assert (got[0] == 0).all()
             G = hq // hkv
             for i in range(c.info["n_q_local"]):     # ctx_len 1 -> the V row itself
                 g = c.info["kv_head0"] + i // G
                 assert np.array_equal(got[1, i], bf16_bits_to_f64(c.V[c.seq_off[1], g]))
     finally:
-        kv.kv_set_option("variant", 0)
+        kv.kv_set_option("heads_per_wave", 0)
 
 
-def test_long_sequences_cut_over_every_wavefront_head_groups():
+@pytest.mark.parametrize("merge_mode", [0, 1, 2])
+def test_long_sequences_cut_over_every_wavefront_head_groups(merge_mode):
     """DP view, four heads per wavefront: two head groups of one long sequence cut over all
-    wavefronts (hundreds of pieces per pair, the merge kernel's long-list grid), next to a short
+    wavefronts (hundreds of pieces per pair: the merge kernel's long-list grid by default, one
+    wavefront walking the whole list when the main kernel is made to finish it), next to a short
     sequence whose pairs are single pieces."""
     w = wl.Workload("long4", 73, 32, 8, 128, 16, 3, "x", ())
     ctx = np.array([9, 30011, 200], dtype=np.int32)
     c = make_case(w, (LAYOUT_DP, 1, 0), ctx)
     want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
-    got = run_gpu_decode(c, gpu_view(w, (LAYOUT_DP, 1, 0)))
-    check_close(got, want, "long sequence, head groups")
+    kv.kv_set_option("merge_mode", merge_mode)
+    try:
+        got = run_gpu_decode(c, gpu_view(w, (LAYOUT_DP, 1, 0)))
+    finally:
+        kv.kv_set_option("merge_mode", 0)
+    check_close(got, want, f"long sequence, head groups, merge mode {merge_mode}")
 
 
 @pytest.mark.parametrize("cost", [0, 8, 64])
@@ -203,57 +225,66 @@ def test_uneven_shares_between_xcds(skew):
         kv.kv_set_option("xcd_skew", -1)
 
 
-def test_one_long_sequence_cut_over_every_wavefront():
+@pytest.mark.parametrize("merge_mode", [0, 1])
+def test_one_long_sequence_cut_over_every_wavefront(merge_mode):
     """A single (sequence, head) pair cut over every wavefront of the launch (about a thousand
-    pieces to merge), twice in a row on one uninitialised workspace, which then serves a call of
-    another kernel and another shape."""
+    pieces to combine), twice in a row on one workspace that is garbage apart from the zeroed
+    arrival words, which then serves a call of another kernel and another shape."""
     w = wl.Workload("long1", 70, 32, 8, 128, 16, 2, "x", ())
     ctx = np.array([40000, 3], dtype=np.int32)
     triple = (LAYOUT_TP, 8, 3)
     c = make_case(w, triple, ctx)
     view = gpu_view(w, triple)
-    ws = torch.full((kv.paged_decode_attn_workspace_bytes(view, 2, 40000),), 0xAB, dtype=torch.uint8,
-                    device=DEV)
+    ws = poisoned_workspace(kv.paged_decode_attn_workspace_bytes(view, 2, 40000), 0xAB)
     want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
     q, pool = dev_u16(c.q), dev_u16(c.pool)
     table, n = torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
-    for _ in range(2):
-        out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws)
+    kv.kv_set_option("merge_mode", merge_mode)
+    try:
+        for _ in range(2):
+            out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws)
+            torch.cuda.synchronize()
+            check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence")
+            assert sync_words_are_zero(ws)
+        # same workspace, chunked vector-ALU kernel on a different shape, then the even-split kernel again
+        c2 = make_case(TINY, (LAYOUT_TP, 2, 1))
+        ws2 = poisoned_workspace(max(ws.numel(), kv.paged_decode_attn_workspace_bytes(gpu_view(TINY, (LAYOUT_TP, 2, 1)), 4, 300)),
+                                 0xCD)
+        kv.kv_set_option("chunk_tokens", 64)
+        out2 = kv.paged_decode_attn(dev_u16(c2.q), dev_u16(c2.pool), torch.from_numpy(c2.table).to(DEV),
+                                    torch.from_numpy(c2.ctx).to(DEV), gpu_view(TINY, (LAYOUT_TP, 2, 1)), 300,
+                                    workspace=ws2)
+        kv.kv_set_option("chunk_tokens", 0)
+        out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws2)
         torch.cuda.synchronize()
-        check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence")
-    # same workspace, chunked vector-ALU kernel on a different shape, then the even-split kernel again
-    c2 = make_case(TINY, (LAYOUT_TP, 2, 1))
-    ws2 = torch.full((max(ws.numel(), kv.paged_decode_attn_workspace_bytes(gpu_view(TINY, (LAYOUT_TP, 2, 1)), 4, 300)),),
-                     0xCD, dtype=torch.uint8, device=DEV)
-    kv.kv_set_option("chunk_tokens", 64)
-    out2 = kv.paged_decode_attn(dev_u16(c2.q), dev_u16(c2.pool), torch.from_numpy(c2.table).to(DEV),
-                                torch.from_numpy(c2.ctx).to(DEV), gpu_view(TINY, (LAYOUT_TP, 2, 1)), 300,
-                                workspace=ws2)
-    kv.kv_set_option("chunk_tokens", 0)
-    out = kv.paged_decode_attn(q, pool, table, n, view, 40000, workspace=ws2)
-    torch.cuda.synchronize()
+    finally:
+        kv.kv_set_option("merge_mode", 0)
+        kv.kv_set_option("chunk_tokens", 0)
     check_close(bf16_bits_to_f64(out2.cpu().numpy().view(np.uint16)),
                 oracle.paged_decode(c2.view, c2.q, c2.pool, c2.table, c2.ctx), "tiny on shared workspace")
     check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, "long sequence after reuse")
+    assert sync_words_are_zero(ws2)
 
 
 def test_repeated_calls_on_one_workspace():
-    """Five calls in a row on one workspace whose first contents are garbage, each compared with
-    the oracle: nothing a call leaves in the workspace may leak into the next one."""
+    """Calls of changing shapes in a row on one workspace (garbage apart from the zeroed arrival
+    words), each compared with the oracle: nothing a call leaves in the workspace may leak into the
+    next one, and every call leaves the arrival words zero."""
     w = wl.Workload("tuned", 71, 32, 8, 128, 16, 9, "x", ())
     ctx = np.array([7000, 4100, 9000, 33, 6000, 8000, 3000, 5111, 1], dtype=np.int32)
-    for triple in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1)]:
-        c = make_case(w, triple, ctx)
-        view = gpu_view(w, triple)
-        ws = torch.full((kv.paged_decode_attn_workspace_bytes(view, len(ctx), 9000),), 0x5A, dtype=torch.uint8,
-                        device=DEV)
+    short = np.array([300, 5000, 0, 1200, 64, 2500, 17, 800, 4000], dtype=np.int32)
+    views = {t: gpu_view(w, t) for t in [(LAYOUT_DP, 1, 0), (LAYOUT_TP, 2, 1), (LAYOUT_TP, 8, 6)]}
+    ws = poisoned_workspace(max(kv.paged_decode_attn_workspace_bytes(v, len(ctx), 9000) for v in views.values()), 0x5A)
+    for call, (triple, lens) in enumerate([((LAYOUT_DP, 1, 0), ctx), ((LAYOUT_DP, 1, 0), ctx), ((LAYOUT_TP, 8, 6), short),
+                                           ((LAYOUT_TP, 2, 1), ctx), ((LAYOUT_TP, 8, 6), ctx), ((LAYOUT_DP, 1, 0), short),
+                                           ((LAYOUT_TP, 2, 1), short)]):
+        c = make_case(w, triple, lens)
         want = oracle.paged_decode(c.view, c.q, c.pool, c.table, c.ctx)
-        q, pool = dev_u16(c.q), dev_u16(c.pool)
-        table, n = torch.from_numpy(c.table).to(DEV), torch.from_numpy(c.ctx).to(DEV)
-        for call in range(5):
-            out = kv.paged_decode_attn(q, pool, table, n, view, 9000, workspace=ws)
-            torch.cuda.synchronize()
-            check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, f"{triple} call {call}")
+        out = kv.paged_decode_attn(dev_u16(c.q), dev_u16(c.pool), torch.from_numpy(c.table).to(DEV),
+                                   torch.from_numpy(c.ctx).to(DEV), views[triple], int(lens.max()), workspace=ws)
+        torch.cuda.synchronize()
+        check_close(bf16_bits_to_f64(out.cpu().numpy().view(np.uint16)), want, f"{triple} call {call}")
+        assert sync_words_are_zero(ws), f"call {call} left arrival words behind"
 
 
 @pytest.mark.parametrize("p,r", [(2, 1), (4, 2), (8, 0)])

@@ -61,7 +61,7 @@ def check(got, want, what):
 @pytest.fixture
 def default_options():
     yield
-    for k, v in {"variant": 0, "chunk_tokens": 0, "xcd_skew": -1, "piece_cost": -1}.items():
+    for k, v in {"heads_per_wave": 0, "merge_mode": 0, "chunk_tokens": 0, "xcd_skew": -1, "piece_cost": -1}.items():
         kv.kv_set_option(k, v)
 
 
@@ -74,7 +74,8 @@ def test_random_decode_cases(seed, default_options):
         ctx = draw_lens(rng, batch, int(rng.choice([300, 1500, 5000])))
         if rng.integers(0, 5) == 0:
             ctx[int(rng.integers(0, batch))] = 0          # an empty context among the others
-        opts = {"variant": int(rng.integers(0, 8)), "chunk_tokens": int(rng.choice([0, 0, 0, 64, 128, 512])),
+        opts = {"heads_per_wave": int(rng.integers(0, 2)), "merge_mode": int(rng.integers(0, 3)),
+                "chunk_tokens": int(rng.choice([0, 0, 0, 64, 128, 512])),
                 "xcd_skew": int(rng.choice([-1, 0, 64, 200])), "piece_cost": int(rng.choice([-1, 0, 8, 40]))}
         what = f"seed {seed} case {it}: hq {hq} hkv {hkv} block {bb} view {triple} ctx {ctx.tolist()} {opts}"
         w = wl.Workload("sweep", 40 + it, hq, hkv, 128, bb, batch, "x", ())
