@@ -26,8 +26,19 @@ def ensure_built():
         build()
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(case, target_seconds=10.0):
-    """The oracle as it stands, timed on the host cores on the same inputs (pool copy 0)."""
+    """The oracle as it stands, timed on the host cores on the same inputs (pool copy 0): full passes
+    on all its threads, then one pass of a quarter of the sequences on a single thread for scale."""
     import numpy as np
     import oracle
     w = case.workload
@@ -43,12 +54,25 @@ def cpu_baseline(case, target_seconds=10.0):
         ref = oracle.paged_decode(view, q, pool, table, ctx)
         spent += time.perf_counter() - t0
         reps += 1
+    # one thread, every fourth sequence (the rest given length 0), scaled by the token share
+    sub = np.where(np.arange(len(ctx)) % 4 == 0, ctx, 0).astype(np.int32)
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        oracle.paged_decode(view, q, pool, table, sub)
+        one = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(threads)
+    one_full = one * float(ctx.sum()) / max(float(sub.sum()), 1.0)
     return {
         "value": round(case.kv_bytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": threads,
-        "kind": "oracle",
-        "sample": f"all {len(ctx)} sequences of the workload, {reps} full passes, "
+        "kind": "oracle", "cpu_model": cpu_model(),
+        "seconds_per_pass": round(spent / reps, 4),
+        "one_thread_s": round(one_full, 3),
+        "sample": f"all {len(ctx)} sequences of the workload, {reps} full passes on {threads} threads, "
                   f"{spent / reps:.2f} s per pass, {spent * threads:.0f} core-seconds in all "
-                  f"(fp64, OpenMP over (sequence, query head))",
+                  f"(fp64, OpenMP over (sequence, query head)); one_thread_s: every fourth sequence on one "
+                  f"thread ({one:.2f} s), scaled to the whole batch by tokens",
     }, ref
 
 
@@ -182,8 +206,17 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     gbps = case.kv_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # --- per-kernel durations from HIP events on the launch stream (separate pass): the kernels'
-    #     own start and end times, taken by the launch itself -----------------------------------------
+    # --- single calls between pairs of events on the launch stream: median and minimum beside the mean
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (e0, e1) in enumerate(ev):
+        e0.record()
+        run(i)
+        e1.record()
+    torch.cuda.synchronize()
+    call_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in ev)
+
+    # --- per-kernel durations from HIP events on the launch stream (separate pass, switched on after
+    #     the warm-up above): the kernels' own start and end times, taken by the launch itself ------
     kv.kv_profile_enable(True)
     for i in range(args.steps):
         run(i)
@@ -194,11 +227,15 @@ def main():
     main_avg_ms = main_ms / max(n_main, 1)
     achieved = case.kv_bytes / (main_avg_ms * 1e-3) / 1e9
 
-    traffic = None
+    # HBM traffic per launch is not measured in this run: it comes from the committed counter
+    # summaries (profiles/), keyed by workload and view; null where no summary covers the case
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get(f"{w.name}:{','.join(map(str, triple))}")
+            traffic_source = "profiles/traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the copy probe)" \
+                if traffic is not None else None
         except Exception:
             traffic = None
 
@@ -206,6 +243,7 @@ def main():
         "metric": "decode-attn KV bytes/s", "value": round(gbps, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "us_per_layer": round(ms_per_step * 1e3, 2),
+        "us_per_call_median": round(call_us[len(call_us) // 2], 2), "us_per_call_min": round(call_us[0], 2),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -219,8 +257,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "paged decode main kernel",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "avg_kernel_us": round(main_avg_ms * 1e3, 2),
-                     "merge_kernel_us": round(merge_ms / max(n_merge, 1) * 1e3, 2),
+                     "merge_kernel_us": round(merge_ms / max(n_merge, 1) * 1e3, 2) if n_merge else None,
                      "algorithmic_bytes_per_launch": case.kv_bytes},
     }
     result["roofline"]["measured_stream_ceiling"] = stream_ceiling()
@@ -241,25 +280,41 @@ def main():
         extras = {}
         del case, run
         torch.cuda.empty_cache()
-        # kv_repack: the 8B batch-128 lengths, DP layout -> rank-0 TP4 layout and back
+        # kv_repack: the 8B batch-128 lengths, DP layout -> rank-0 TP4 layout and back; and the two
+        # 131072-token sequences of the long-context mix, DP -> rank-0 TP4
+        def timed_repack(fn, steps):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            kv.kv_profile_enable(True)           # after the warm-up: only the timed launches are recorded
+            ms = harness.time_calls(lambda i: fn(), steps, 0)
+            k_ms, k_n = kv.kv_profile_read(kv.KV_PROF_REPACK)
+            kv.kv_profile_enable(False)
+            return ms, k_ms / max(k_n, 1)
+
+        def repack_row(moved, ms, k_ms):
+            return {"us": round(ms * 1e3, 2), "kernel_us": round(k_ms * 1e3, 2),
+                    "read_plus_write_GBps": round(2 * moved / (ms * 1e-3) / 1e9, 1),
+                    "roofline": {"bound": "hbm", "achieved": round(2 * moved / (k_ms * 1e-3) / 1e9, 1),
+                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                 "frac": round(2 * moved / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}}
+
+        steps = max(50, args.steps // 2)
         rw = wl.WORKLOADS["llama8b_tp_b128"]
         rc = harness.build_repack_case(rw, (0, 1, 0), (1, 4, 0))
-        steps = max(5, args.steps // 5)
-        kv.kv_profile_enable(True)
-        fwd_ms = harness.time_calls(lambda i: rc.forward(), steps, 3)
-        f_ms, f_n = kv.kv_profile_read(kv.KV_PROF_REPACK)
-        bwd_ms = harness.time_calls(lambda i: rc.backward(), steps, 3)
-        b_ms, b_n = kv.kv_profile_read(kv.KV_PROF_REPACK)
-        kv.kv_profile_enable(False)
-        extras["kv_repack"] = {
-            "workload": rw.name, "moved_bytes": rc.moved_bytes,
-            "dp_to_tp4_r0": {"us": round(fwd_ms * 1e3, 2),
-                             "read_plus_write_GBps": round(2 * rc.moved_bytes / (fwd_ms * 1e-3) / 1e9, 1),
-                             "kernel_us": round(f_ms / max(f_n, 1) * 1e3, 2)},
-            "tp4_r0_to_dp": {"us": round(bwd_ms * 1e3, 2),
-                             "read_plus_write_GBps": round(2 * rc.moved_bytes / (bwd_ms * 1e-3) / 1e9, 1),
-                             "kernel_us": round(b_ms / max(b_n, 1) * 1e3, 2)},
-        }
+        fwd = timed_repack(rc.forward, steps)
+        bwd = timed_repack(rc.backward, steps)
+        extras["kv_repack"] = {"workload": rw.name, "moved_bytes": rc.moved_bytes, "calls_timed": steps,
+                               "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd),
+                               "tp4_r0_to_dp": repack_row(rc.moved_bytes, *bwd)}
+        del rc
+        torch.cuda.empty_cache()
+        lw = wl.WORKLOADS["llama8b_tp4_longmix"]
+        rc = harness.build_repack_case(lw, (0, 1, 0), (1, 4, 0), np.array([131072, 131072], dtype=np.int32))
+        fwd = timed_repack(rc.forward, steps)
+        extras["kv_repack_long"] = {"workload": lw.name, "what": "the two 131072-token sequences, DP -> TP4 rank 0",
+                                    "moved_bytes": rc.moved_bytes, "calls_timed": steps,
+                                    "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd)}
         del rc
         torch.cuda.empty_cache()
         others = []
@@ -268,10 +323,24 @@ def main():
             for tr in ow.views:
                 oc = harness.build_decode_case(ow, tr, n_copies=args.copies)
                 orun = oc.prepared()
-                ms = harness.time_calls(orun, max(10, args.steps // 2), 5)
-                others.append({"workload": name, "view": list(tr), "us_per_layer": round(ms * 1e3, 2),
+                ms = harness.time_calls(orun, max(50, args.steps // 2), 10)
+                kv.kv_profile_enable(True)
+                for i in range(20):
+                    orun(i)
+                torch.cuda.synchronize()
+                k_ms, k_n = kv.kv_profile_read(kv.KV_PROF_DECODE_MAIN)
+                m_ms, m_n = kv.kv_profile_read(kv.KV_PROF_DECODE_MERGE)
+                kv.kv_profile_enable(False)
+                k_ms /= max(k_n, 1)
+                others.append({"workload": name, "view": list(tr), "kv_bytes": oc.kv_bytes,
+                               "us_per_layer": round(ms * 1e3, 2),
                                "GBps": round(oc.kv_bytes / (ms * 1e-3) / 1e9, 1),
-                               "pct_hbm_peak": round(100 * oc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)})
+                               "pct_hbm_peak": round(100 * oc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+                               "main_kernel_us": round(k_ms * 1e3, 2),
+                               "merge_kernel_us": round(m_ms / m_n * 1e3, 2) if m_n else None,
+                               "roofline": {"bound": "hbm", "achieved": round(oc.kv_bytes / k_ms / 1e6, 1),
+                                            "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                            "frac": round(oc.kv_bytes / k_ms / 1e6 / HBM_PEAK_GBPS, 4)}})
                 del oc, orun
                 torch.cuda.empty_cache()
         extras["other_workloads"] = others
@@ -296,8 +365,11 @@ def main():
                                    ("1 chunk of 512 tokens on 131072 cached (key range split over workgroups)",
                                     (0, 1, 0), [131072], [512])):
             pc = harness.build_prefill_case(w8, tr, ctx, ql)
+            for i in range(3):
+                pc.run(i)
+            torch.cuda.synchronize()
             kv.kv_profile_enable(True)
-            ms = harness.time_calls(pc.run, 10, 2)
+            ms = harness.time_calls(pc.run, 10, 0)
             k_ms, k_n = kv.kv_profile_read(kv.KV_PROF_PREFILL)
             kv.kv_profile_enable(False)
             k_ms /= max(k_n, 1)
