@@ -6,21 +6,37 @@
 // copied: the kernel addresses the full matrix with its own leading dimension.
 //
 // Shaped for decode batches (M up to a few hundred rows): the weight slice is streamed from HBM
-// once per 64 batch rows and is the dominant traffic; x is small, but every weight row needs all
-// of it, so it must be shared: a workgroup of four wavefronts owns 64 logical weight rows (16 per
-// wavefront) x 64 batch rows and walks its part of the input dimension in slabs of 128.  The x
-// slab (64 rows x 128) is staged in LDS once per workgroup, laid out in MFMA operand order so
-// that each B operand is one contiguous kilobyte, and every wavefront accumulates
+// once per 64 batch rows and is the only traffic that matters; x is small, but every weight row
+// needs all of it, so the workgroup shares it through LDS.  A workgroup of four wavefronts owns
+// 16 RB logical weight rows (RB = 1 or 2 blocks of 16) x 64 batch rows over the whole input
+// dimension (or its share of it), walked in slabs of 128 input features.  With RB row blocks the
+// 4 / RB wavefronts of a row block each take a part of every slab and add up through LDS once, at
+// the end, so no output tile is cut over workgroups unless the launch would otherwise be too small
+// to fill the chip: partial tiles cost as much traffic as the weights they stand for at these
+// batch sizes.  RB is the largest that still gives about two hundred workgroups.
+//
+// The walk is one continuous stream.  A load instruction fetches four rows, 256 contiguous bytes of
+// each (64-byte pieces of a row per instruction, as the operand arrangement would ask for, halve the
+// rate at which HBM delivers the weights), into a ring of registers four slabs deep; a slab's
+// requests are issued three slabs before it is used, and every round issues exactly one slab's
+// worth, rounds past the end included (those ask for 16 bytes and multiply by zero): with nothing
+// conditional about the loads the compiler's count of outstanding requests is exact, and a round
+// waits for its own slab only.  Arrived rows go into one of two LDS buffers, XOR-swizzled so that
+// the row-wise writes and the operand-wise reads are both free of bank conflicts; one barrier per
+// slab (a bare one: the fences of __syncthreads() would drain the request queue); the matrix
+// instructions of a slab run in the round after, while the next slab's operand reads are under way.
+// Every workgroup starts its walk at another slab, so that the workgroups do not ask for the same
+// column range of all rows at the same time.
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
-// with 16x16x32 bf16 MFMA.  Its 16 weight rows are fetched as they lie in memory (a load
-// instruction covers four rows x 256 contiguous bytes) and pass through a wavefront-private,
-// XOR-swizzled LDS buffer into the A-operand arrangement.
-// The walk is paced by memory latency, not bandwidth (per-workgroup timestamps: one round trip
-// under this load is 4-5 us), so the loads of four slabs (a chunk: 64 KiB of W and 64 KiB of x
-// per workgroup) are all issued before anything waits, and the input dimension is cut over
-// `splits` workgroups (grid.z) so that a workgroup has about two chunks: each then leaves an fp32
-// partial tile in the workspace and a second, small kernel adds the splits in a fixed order and
-// rounds to bf16 (deterministic; no atomics).
+// with 16x16x32 bf16 MFMA, fp32 accumulation, one rounding to bf16 at the end.  When the input
+// dimension is cut over `splits` workgroups (small slices only), each leaves an fp32 partial tile in
+// the workspace and a second, small kernel adds the splits in a fixed order (deterministic).
+//
+// Where the time goes (measured by replacing the requests by idle ones): on the 8B projections at
+// M = 64 the kernel takes 16-19 us with no memory traffic at all.  A round costs a workgroup about
+// 0.45 us: 24 KiB written to and 40 KiB read from LDS, eight matrix instructions per wavefront, and
+// the barrier keeps the four wavefronts of a compute unit in the same phase, so LDS and matrix
+// pipe take turns instead of overlapping.  The weight stream itself is not the limit yet.
 #include <string.h>
 
 #include "decode_common.h"
@@ -30,10 +46,8 @@ using namespace kvdec;
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kTileRows = 64;   // logical weight rows per workgroup: 16 per wavefront
 constexpr int kColBlocks = 4;   // 16-row blocks of x per workgroup
 constexpr int kSlab = 128;      // input features per slab
-constexpr int kChunk = 4;       // slabs whose loads a workgroup issues together
 
 struct linear_args {
     const uint16_t* x;
@@ -51,118 +65,207 @@ struct linear_args {
     float* part;            // [splits][M][Nl] fp32 when splits > 1
 };
 
-__global__ __launch_bounds__(kThreads, 2) void linear_view_kernel(linear_args p)
+// s_waitcnt vmcnt(N), N <= 63, leaving the other counters alone
+template <int N>
+__device__ __forceinline__ void wait_vm()
 {
-    // x slabs of one chunk in operand order: piece (kk, cb, quad, c) = x[16 cb + c][32 kk + 8 quad .. + 8)
-    // of a slab sits at ((kk * 4 + cb) * 4 + quad) * 16 + (c ^ (4 kk + quad)): a B operand is one
-    // contiguous kilobyte, and the XOR spreads the row-wise staging writes over all banks
-    __shared__ kv_u32x4 s_x[kChunk][4 * kColBlocks * 64];
-    // weight rows of one slab, per wavefront: piece c (16 bytes) of row t at t * 16 + (c ^ t)
-    __shared__ kv_u32x4 s_w[kThreads / 64][256];
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+// wait until at most `slabs` slabs of OPS loads each are outstanding
+template <int OPS>
+__device__ __forceinline__ void wait_slabs(int slabs)
+{
+    switch (slabs) {
+        case 0: wait_vm<0>(); break;
+        case 1: wait_vm<OPS>(); break;
+        case 2: wait_vm<2 * OPS>(); break;
+        case 3: wait_vm<3 * OPS>(); break;
+        case 4: wait_vm<4 * OPS>(); break;
+        case 5: wait_vm<5 * OPS>(); break;
+        case 6: wait_vm<6 * OPS>(); break;
+        default: wait_vm<(7 * OPS > 63 ? 63 : 7 * OPS)>(); break;
+    }
+}
+
+// Workgroup barrier without the memory fences of __syncthreads(): those would make every wavefront
+// wait for ALL its outstanding loads, the seven slabs in flight included.  What has to be complete
+// at this barrier is stated by the caller's own vmcnt wait (the slab about to be consumed) and by the
+// LDS reads of the previous slab having returned to the matrix instructions that used them.
+__device__ __forceinline__ void stream_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int RB>
+__global__ __launch_bounds__(kThreads, 2) void linear_stream_kernel(linear_args p)
+{
+    constexpr int KP = 4 / RB;        // wavefronts sharing a row block, each a part of every slab
+    constexpr int KK = 4 / KP;        // 32-wide steps of a slab per wavefront
+    constexpr int NR = 4;             // slabs in the register ring: NR - 1 requested ahead (even)
+    // A slab in LDS: rows of 16 16-byte pieces (x: 64 batch rows; w: the workgroup's 16 RB weight
+    // rows), piece q of row t kept at position q ^ (t % 16): the row-wise staging writes and the MFMA
+    // operand reads (lane (r, quad): row r, piece 4 kk + quad) both touch every bank once per 16 lanes.
+    __shared__ kv_u32x4 s_x[2][1024];
+    __shared__ kv_u32x4 s_w[2][256 * RB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, quad = lane >> 4;
+    const int rb = wave % RB, kp = wave / RB;
     const int m0 = blockIdx.x * (16 * kColBlocks);
-    const int n0 = blockIdx.y * kTileRows;
+    const int n0 = blockIdx.y * (16 * RB);
 
-    // the 64 logical rows of this workgroup lie in one segment (segment sizes are multiples of 64)
+    // the rows of this workgroup lie in one segment (segment sizes are multiples of 64)
     int seg = 0;
     while (seg + 1 < p.n_seg && n0 >= p.seg_first[seg + 1]) ++seg;
     const int64_t phys0 = p.seg_start[seg] + (n0 - p.seg_first[seg]);
-    // load instruction u of a slab: row 4 u + quad of the wavefront's 16, piece r of its 16
-    const char* wbase = reinterpret_cast<const char*>(p.w + (phys0 + 16 * wave + quad) * p.ldw + p.col_start) + r * 16;
-    const int64_t w_step4 = 4 * p.ldw * 2;   // bytes between rows 4 apart
-    kv_u32x4* const sw = s_w[wave];
 
-    // staging: thread t moves pieces t, t + 256, t + 512, t + 768 of a slab; piece id = 16 row + q,
-    // q = 4 kk + quad the 16-byte piece within the row's 128 elements (rows past M repeat the last)
+    // staging: a load instruction covers four rows, 256 contiguous bytes of each: lane = 16 g + pos
+    // fetches piece pos of row 4 u + g.  x: wavefront w stages batch rows 16 w .. 16 w + 15 (rows past M
+    // repeat the last one); weights: wavefront w stages rows 4 (RB w + i) .. + 3, i < RB
+    const int g = lane >> 4, pos = lane & 15;
     const char* xsrc[4];
     int xdst[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
-        xsrc[i] = reinterpret_cast<const char*>(p.x + (int64_t)min(m0 + row, p.M - 1) * p.ldx) + q * 16;
-        xdst[i] = (((q >> 2) * kColBlocks + (row >> 4)) * 4 + (q & 3)) * 16 + ((row & 15) ^ q);
+    for (int u = 0; u < 4; ++u) {
+        const int row = 16 * wave + 4 * u + g;
+        xsrc[u] = reinterpret_cast<const char*>(p.x + (int64_t)min(m0 + row, p.M - 1) * p.ldx) + (pos << 4);
+        xdst[u] = row * 16 + (pos ^ (row & 15));
+    }
+    const char* wsrc[RB];
+    int wdst[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int row = 4 * (RB * wave + i) + g;
+        wsrc[i] = reinterpret_cast<const char*>(p.w + (phys0 + row) * p.ldw + p.col_start) + (pos << 4);
+        wdst[i] = row * 16 + (pos ^ (row & 15));
     }
 
-    // this workgroup's slabs: [step, last)
+    // this workgroup's slabs: [first, first + n)
     const int total = p.Kl / kSlab;
     const int per_split = (total + p.splits - 1) / p.splits;
-    int step = (int)blockIdx.z * per_split;
-    const int last = min(total, step + per_split);
+    const int first = (int)blockIdx.z * per_split;
+    const int n = min(total, first + per_split) - first;
+
+    // Every workgroup starts its walk at another slab and wraps around, so that at any moment the
+    // workgroups ask for different column ranges: rows are a power of two apart, and the same columns
+    // of all rows share a few memory channels.
+    const int rot = (int)((blockIdx.y * 5u + blockIdx.x * 3u) % (unsigned)n);
+    // The walk is written without a single conditional load: every round requests exactly one slab
+    // (rounds past the end request 16 bytes of x, the same for all lanes, and multiply by zero).  The
+    // compiler then knows in every round that the registers it is about to use were requested NR - 1
+    // requests ago and waits for exactly those; with requests that may or may not have been issued it
+    // has to assume the worst and drains the whole queue.
+    kv_u32x4 x_reg[NR][4], w_reg[NR][RB];
+    auto issue = [&](int j, int slot) {   // loads of the j-th slab of this workgroup's walk into ring slot `slot`
+        // (address arithmetic instead of a choice between two pointers: a choice on a condition that
+        // is the same for the whole wavefront is compiled into two paths with a load and a wait each)
+        const int64_t keep = j < n ? (int64_t)-1 : 0;
+        int jr = j + rot;
+        if (jr >= n) jr -= n;
+        const int64_t off = (int64_t)(first + jr) * (kSlab * 2);
+        const char* idle = reinterpret_cast<const char*>(p.x);
+#pragma unroll
+        for (int i = 0; i < RB; ++i)
+            w_reg[slot][i] = __builtin_nontemporal_load(
+                reinterpret_cast<const kv_u32x4*>(idle + (((wsrc[i] + off) - idle) & keep)));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            x_reg[slot][u] = *reinterpret_cast<const kv_u32x4*>(idle + (((xsrc[u] + off) - idle) & keep));
+    };
 
     f32x4 acc[kColBlocks];
 #pragma unroll
     for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // A chunk is up to kChunk slabs.  All of a chunk's loads (weights first, then x) are issued
-    // before anything waits: the walk along the input dimension is paced by memory latency, so a
-    // workgroup should need as few round trips as it can, and the splits are chosen to give it one
-    // or two chunks.
-    kv_u32x4 a_st[kChunk][4], x_st[kChunk][4];
-    auto compute = [&](int j) {
+    // Round j: slab j goes from this wavefront's registers into LDS buffer j % 2 and its ring slot
+    // takes the next request; after the barrier the operands of slab j are read from LDS and, while
+    // those reads are under way, the matrix instructions of slab j - 1 run on the operands read in the
+    // round before: with one wavefront per SIMD nothing else would hide the LDS latency.
+    kv_u32x4 a_op[2][KK], b_op[2][KK][kColBlocks];
+    auto read_operands = [&](int buf, int which, bool real) {
+        const kv_u32x4* xb = s_x[buf];
+        const kv_u32x4* wrow = s_w[buf] + (16 * rb + r) * 16;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int row = 4 * u + quad;
-            sw[row * 16 + (r ^ row)] = a_st[j][u];
+        for (int t = 0; t < KK; ++t) {
+            const int q = 4 * (kp * KK + t) + quad;
+            a_op[which][t] = wrow[q ^ r];
+            if (!real) a_op[which][t] = kv_u32x4{0u, 0u, 0u, 0u};   // a round past the end adds nothing
+#pragma unroll
+            for (int cb = 0; cb < kColBlocks; ++cb) b_op[which][t][cb] = xb[(16 * cb + r) * 16 + (q ^ r)];
         }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const kv_u32x4 a = sw[r * 16 + ((4 * kk + quad) ^ r)];
-#pragma unroll
-            for (int cb = 0; cb < kColBlocks; ++cb) {
-                const kv_u32x4 b = s_x[j][(kk * kColBlocks + cb) * 64 + quad * 16 + (r ^ (4 * kk + quad))];
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), acc[cb], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
     };
-    for (bool first = true; step < last; step += kChunk, first = false) {
-        const int n_slabs = min(kChunk, last - step);
-        const int64_t off = (int64_t)step * (kSlab * 2);
+    auto multiply = [&](int which) {
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j)
-            if (j < n_slabs) {
+        for (int t = 0; t < KK; ++t)
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    a_st[j][u] = __builtin_nontemporal_load(
-                        reinterpret_cast<const kv_u32x4*>(wbase + off + j * (kSlab * 2) + u * w_step4));
-            }
+            for (int cb = 0; cb < kColBlocks; ++cb)
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_op[which][t]),
+                                                                  as_bf16x8(b_op[which][t][cb]), acc[cb], 0, 0, 0);
+    };
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j)
-            if (j < n_slabs) {
+    for (int t = 0; t < KK; ++t) {
+        a_op[1][t] = kv_u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    x_st[j][i] = *reinterpret_cast<const kv_u32x4*>(xsrc[i] + off + j * (kSlab * 2));
-            }
-        if (!first) __syncthreads();   // the previous chunk's operands have been read
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j)
-            if (j < n_slabs) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s_x[j][xdst[i]] = x_st[j][i];
-            }
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j)
-            if (j < n_slabs) compute(j);
+        for (int cb = 0; cb < kColBlocks; ++cb) b_op[1][t][cb] = kv_u32x4{0u, 0u, 0u, 0u};
     }
 
-    // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 wave + 4 quad + i]
+#pragma unroll
+    for (int j = 0; j < NR - 1; ++j) issue(j, j);
+    for (int j0 = 0; j0 < n; j0 += NR) {
+#pragma unroll
+        for (int jj = 0; jj < NR; ++jj) {
+            const int j = j0 + jj;
+            kv_u32x4* xb = s_x[jj & 1];
+            kv_u32x4* wb = s_w[jj & 1];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) wb[wdst[i]] = w_reg[jj][i];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xb[xdst[u]] = x_reg[jj][u];
+            issue(j + NR - 1, (jj + NR - 1) % NR);
+            // this wavefront's pieces are written, and its operand reads of the round before (from the
+            // other buffer, which the next round overwrites) have returned
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+            stream_barrier();
+            read_operands(jj & 1, jj & 1, j < n);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply((jj + 1) & 1);
+        }
+    }
+    multiply((NR - 1) & 1);   // the last round's slab (NR is even: its operands are in set 1)
+
+    // the wavefronts of a row block add up (buffers are free once everybody has left the loop)
+    if (KP > 1) {
+        __syncthreads();
+        f32x4* red = reinterpret_cast<f32x4*>(&s_x[0][0]);   // [wave][cb][lane]
+        if (kp > 0) {
+#pragma unroll
+            for (int cb = 0; cb < kColBlocks; ++cb) red[(wave * kColBlocks + cb) * 64 + lane] = acc[cb];
+        }
+        __syncthreads();
+        if (kp > 0) return;
+#pragma unroll
+        for (int k = 1; k < KP; ++k)
+#pragma unroll
+            for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] += red[((k * RB + rb) * kColBlocks + cb) * 64 + lane];
+    }
+
+    // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 rb + 4 quad + i]
 #pragma unroll
     for (int cb = 0; cb < kColBlocks; ++cb) {
         const int m = m0 + 16 * cb + r;
         if (m >= p.M) continue;
-        const int n = n0 + 16 * wave + 4 * quad;
+        const int nn = n0 + 16 * rb + 4 * quad;
         if (p.splits > 1) {
-            *reinterpret_cast<f32x4*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + n) = acc[cb];
+            *reinterpret_cast<f32x4*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + nn) = acc[cb];
         } else {
             uint2 pk;
             pk.x = pack_bf16x2(acc[cb][0], acc[cb][1]);
             pk.y = pack_bf16x2(acc[cb][2], acc[cb][3]);
-            *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + n) = pk;
+            *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + nn) = pk;
         }
     }
 }
@@ -194,21 +297,29 @@ __global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
     *reinterpret_cast<uint2*>(p.y + m * p.ldy + n) = pk;
 }
 
-// Workgroups sharing the input dimension of one output tile.  Measured on the Llama-8B
-// projections (batch 16..256, TP 1..8): the optimum is flat around two chunks per workgroup; more
-// splits shorten the chain of memory round trips but their partial tiles cost as much again, fewer
-// leave compute units idle.  So: two chunks each, more splits only while the launch would have
-// fewer than 192 workgroups, fewer when it would have more than 1024; at most 16.
-int pick_splits(int64_t tiles, int total_slabs)
+// Row blocks per workgroup and workgroups sharing the input dimension of one output tile.
+// Whole tiles per workgroup wherever that gives about two hundred workgroups (the launch has to
+// keep enough bytes in flight, not to occupy every compute unit); the input dimension is cut only
+// for slices too small for that, and then into as few parts as fill half the chip.
+struct linear_cfg {
+    int rb, splits;
+};
+linear_cfg pick_cfg(int64_t m_tiles, int64_t n_l, int total_slabs)
 {
-    int s = (total_slabs + 2 * kChunk - 1) / (2 * kChunk);
-    while (s < 16 && s < total_slabs && tiles * s < 192) ++s;
-    while (s > 1 && tiles * s > 1024) --s;
+    linear_cfg c = {1, 1};
+    for (int rb = 2; rb >= 1; rb >>= 1) {
+        c.rb = rb;
+        if (m_tiles * (n_l / (16 * rb)) >= 192) break;
+    }
+    const int64_t tiles = m_tiles * (n_l / (16 * c.rb));
+    int s = 1;
+    while (s < 16 && s < total_slabs && tiles * s < 128) ++s;
     const int64_t forced = kv_option_linear_splits();
     if (forced > 0) s = (int)forced;
     s = s > 16 ? 16 : s;
     s = s > total_slabs ? total_slabs : s;
-    return s < 1 ? 1 : s;
+    c.splits = s < 1 ? 1 : s;
+    return c;
 }
 
 int64_t view_rows(const kv_weight_view* view)
@@ -225,8 +336,8 @@ extern "C" size_t kv_linear_view_workspace_bytes(const kv_weight_view* view, int
     if (!view || M <= 0 || view->n_segments < 1 || view->n_segments > 3 || view->col_count <= 0) return 0;
     const int64_t n_l = view_rows(view);
     if (n_l <= 0) return 0;
-    const int64_t tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks) * (n_l / kTileRows);
-    const int splits = pick_splits(tiles > 0 ? tiles : 1, (int)(view->col_count / kSlab));
+    const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
+    const int splits = pick_cfg(m_tiles, n_l, (int)(view->col_count / kSlab)).splits;
     return splits > 1 ? (size_t)splits * M * n_l * 4 : 0;
 }
 
@@ -293,7 +404,7 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
         view->col_count > 0x7fffffff)
         return KV_ERR_UNSUPPORTED;
     for (int i = 0; i < view->n_segments; ++i)
-        if (view->row_count[i] % kTileRows != 0) return KV_ERR_UNSUPPORTED;
+        if (view->row_count[i] % 64 != 0) return KV_ERR_UNSUPPORTED;
     linear_args p;
     p.x = (const uint16_t*)x;
     p.ldx = ldx;
@@ -315,9 +426,10 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     p.seg_first[3] = first;
     for (int i = view->n_segments; i < 4; ++i) p.seg_first[i] = first;
     const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
-    const int64_t n_tiles = n_l / kTileRows;
+    const linear_cfg cfg = pick_cfg(m_tiles, n_l, p.Kl / kSlab);
+    const int64_t n_tiles = n_l / (16 * cfg.rb);
     if (m_tiles > 0x7fffffff || n_tiles > 65535) return KV_ERR_UNSUPPORTED;
-    p.splits = pick_splits(m_tiles * n_tiles, p.Kl / kSlab);
+    p.splits = cfg.splits;
     p.part = (float*)workspace;
     if (p.splits > 1) {
         if (!workspace || ((uintptr_t)workspace & 15)) return KV_ERR_INVALID_ARG;
@@ -325,8 +437,9 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     }
     hipStream_t st = (hipStream_t)hip_stream;
     const int slot = kv_prof_begin(KV_PROF_LINEAR, st);
-    hipLaunchKernelGGL(linear_view_kernel, dim3((unsigned)m_tiles, (unsigned)n_tiles, (unsigned)p.splits),
-                       dim3(kThreads), 0, st, p);
+    const dim3 grid((unsigned)m_tiles, (unsigned)n_tiles, (unsigned)p.splits);
+    if (cfg.rb == 2) hipLaunchKernelGGL(linear_stream_kernel<2>, grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL(linear_stream_kernel<1>, grid, dim3(kThreads), 0, st, p);
     if (p.splits > 1) {
         const int64_t quads = (int64_t)M * (n_l / 4);
         hipLaunchKernelGGL(linear_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p);
