@@ -50,6 +50,7 @@ struct prefill_args {
     int32_t group;          // G <= 16 query heads per KV head
     int32_t group_shift;    // log2 of G rounded up to a power of two: rows per token in the tile
     int32_t splits;         // workgroups sharing the key range of one query tile
+    int32_t wgs_per_pair;   // query tiles of the longest chunk x splits: workgroups per (sequence, KV head)
     int64_t rows;           // total_q * n_q_local: rows of the partial arrays
     float* part_o;          // [splits][rows][128] un-normalised sums, when splits > 1
     float* part_ml;         // [splits][rows][2]   (reference maximum in score units, sum of weights)
@@ -87,15 +88,28 @@ __global__ __launch_bounds__(kThreads, R <= 2 ? 3 : 1) void prefill_kernel(prefi
     const int r = lane & 15, quad = lane >> 4;
     const kv_view_dev& v = a.v;
     const int G = a.group;
-    const int s = blockIdx.z, hl = blockIdx.y;
+    // Which (sequence, KV head, query tile, key split) this workgroup takes.  The hardware deals
+    // consecutive workgroups out to the eight XCDs in turn, each with its own L2; every query tile of
+    // a (sequence, head) pair reads that pair's keys and values again, so all tiles of a pair go to
+    // one XCD: workgroup L runs on XCD L % 8 and takes the (L / 8)-th item of that XCD's eighth of the
+    // (pair-major) work list.  A pair's K/V (2 MiB per 4096 tokens) then stays in one 4 MiB L2 while
+    // its tiles are worked on, instead of streaming through all eight.
+    int item;
+    {
+        const int L = (int)blockIdx.x, N = (int)gridDim.x;
+        const int xcd = L & 7, k = L >> 3, base = N >> 3, rem = N & 7;
+        item = xcd * base + min(xcd, rem) + k;
+    }
+    const int pair = item / a.wgs_per_pair, in_pair = item - pair * a.wgs_per_pair;
+    const int s = pair / a.v.n_kv_local, hl = pair - s * a.v.n_kv_local;
     const int tokens_per_wg = (64 * R) >> a.group_shift;
 
     const int n = a.ctx_lens[s];
     const int q0 = a.q_off[s];
     const int q_len = a.q_off[s + 1] - q0;
     // longest tiles first: the last query tile of a sequence sees the most keys
-    const int split = (int)blockIdx.x % a.splits;
-    const int j0 = ((int)gridDim.x / a.splits - 1 - (int)blockIdx.x / a.splits) * tokens_per_wg;
+    const int split = in_pair % a.splits;
+    const int j0 = (a.wgs_per_pair / a.splits - 1 - in_pair / a.splits) * tokens_per_wg;
     if (j0 >= q_len || n <= 0) return;
     const int first_pos = n - q_len;                         // position of the sequence's query 0
     const int j_last = min(j0 + tokens_per_wg, q_len) - 1;   // last query token of this tile
@@ -471,7 +485,10 @@ extern "C" int paged_prefill_attn(const void* q, void* out, const void* kv_pool,
     const int tokens_per_wg = (64 * R) >> a.group_shift;
     const int64_t q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
     if (q_tiles * a.splits > 0x7fffffff) return KV_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)(q_tiles * a.splits), (unsigned)view->n_kv_local, (unsigned)batch);
+    a.wgs_per_pair = (int32_t)(q_tiles * a.splits);
+    const int64_t n_wgs = q_tiles * a.splits * view->n_kv_local * batch;
+    if (n_wgs > 0x7fffffff) return KV_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)n_wgs);
     int slot = kv_prof_begin(KV_PROF_PREFILL, st);
     hipLaunchKernelGGL(prefill_kernel<R>, grid, dim3(kThreads), 0, st, a);
     if (a.splits > 1)
