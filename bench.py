@@ -156,6 +156,11 @@ def main():
                          "SDPA on contiguous K/V for the prefill cases, matmul on the weight slices")
     ap.add_argument("--probe", action="store_true",
                     help="only run the known-traffic streaming kernels (read 1 GiB, copy 1 GiB) and exit")
+    ap.add_argument("--placement", action="store_true",
+                    help="only run the placement probe (which XCD each workgroup index runs on, and how "
+                         "fast each XCD streams its share of 256 MiB) and exit")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="set a library option (kv_set_option) before measuring; may be repeated")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -189,6 +194,31 @@ def main():
     if args.probe:
         print(json.dumps({"probe": stream_ceiling()}))
         return
+    if args.placement:
+        # 256 workgroups (one per compute unit, 1 MiB each) as the decode kernels launch them
+        n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        runs = []
+        for _ in range(6):
+            rec = kv.kv_probe_read_placed(src, n_wg)
+            torch.cuda.synchronize()
+            runs.append(rec.cpu().numpy())
+        runs = runs[1:]                                  # the first launch is the cold one
+        xcc = runs[0][:, 0]
+        same_every_run = all((r[:, 0] == xcc).all() for r in runs)
+        by_rule = bool((xcc == np.arange(n_wg) % 8).all())
+        dur = np.mean([(r[:, 2] - r[:, 1]) * 0.01 for r in runs], axis=0)        # us per workgroup
+        end = np.mean([(r[:, 2] - r[:, 1].min()) * 0.01 for r in runs], axis=0)  # end after the first start
+        per_xcd = {int(x): {"workgroups": int((xcc == x).sum()), "mean_stream_us": round(float(dur[xcc == x].mean()), 2),
+                            "mean_end_us": round(float(end[xcc == x].mean()), 2)} for x in np.unique(xcc)}
+        print(json.dumps({"placement": {"workgroups": n_wg, "bytes": int(src.numel()),
+                                        "xcd_of_workgroup_is_index_mod_8": by_rule,
+                                        "same_in_every_launch": bool(same_every_run),
+                                        "first_16_workgroups_xcd": [int(v) for v in xcc[:16]], "per_xcd": per_xcd}}))
+        return
+    for item in args.option:
+        key, _, val = item.partition("=")
+        kv.kv_set_option(key, int(val))
     w = wl.WORKLOADS[args.workload]
     triple = tuple(int(x) for x in args.view.split(",")) if args.view else w.views[0]
 
@@ -253,7 +283,7 @@ def main():
                    "head_dim": w.head_dim, "block_tokens": case.view.block_tokens,
                    "batch": w.batch, "tokens": int(case.ctx.sum()), "kv_bytes": case.kv_bytes,
                    "pool_copies": args.copies, "storage": "bf16 K/V/q/out", "accumulate": "fp32",
-                   "chunk_tokens": kv.kv_get_option("chunk_tokens")},
+                   "library_options": {k: int(v) for k, _, v in (o.partition("=") for o in args.option)}},
         "roofline": {"bound": "hbm", "kernel": "paged decode main kernel",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,

@@ -382,6 +382,14 @@ int kv_probe_copy(void* dst, const void* src, size_t bytes, int n_workgroups, vo
 int kv_probe_read_blocks(const void* pool, const int32_t* block_ids, int n_ids, int64_t block_bytes,
                          void* sink, int n_workgroups, void* hip_stream);
 
+/* Placement probe: workgroup g reads the g-th of n_workgroups equal contiguous shares of `bytes`
+ * (the shares are rounded down to whole 16-byte pieces per wavefront) and writes three int64 values
+ * to records[3 g ..] (device): the XCD it ran on (hardware register XCC_ID), and its start and end
+ * times in ticks of the 100 MHz constant-rate counter.  Shows how workgroup indices map to XCDs and
+ * whether the XCDs stream at the same rate. */
+int kv_probe_read_placed(const void* src, size_t bytes, int64_t* records, void* sink, int n_workgroups,
+                         void* hip_stream);
+
 const char* kv_strerror(int status);   /* static string, never null */
 const char* kv_last_hip_error(void);   /* text of the last HIP failure seen by this thread */
 const char* kv_version(void);

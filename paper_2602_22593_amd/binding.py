@@ -422,6 +422,18 @@ def kv_probe_copy(dst: torch.Tensor, src: torch.Tensor, n_workgroups: int, strea
            "kv_probe_copy")
 
 
+def kv_probe_read_placed(src: torch.Tensor, n_workgroups: int, stream=None) -> torch.Tensor:
+    """Stream ``src`` once in contiguous per-workgroup shares; returns int64 [n_workgroups][3] on the
+    device: XCD of the workgroup, start tick, end tick (100 MHz)."""
+    L = lib()
+    L.kv_probe_read_placed.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+    rec = torch.zeros((n_workgroups, 3), dtype=torch.int64, device=src.device)
+    _check(L.kv_probe_read_placed(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                  C.c_void_p(rec.data_ptr()), None, n_workgroups, _stream_ptr(stream)),
+           "kv_probe_read_placed")
+    return rec
+
+
 def kv_probe_read_blocks(pool: torch.Tensor, block_ids: torch.Tensor, block_bytes: int,
                          n_workgroups: int, stream=None) -> None:
     """Stream the pool blocks listed in ``block_ids`` (int32, device) once, block by block."""

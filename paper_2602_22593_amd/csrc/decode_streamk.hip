@@ -1343,10 +1343,13 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
     // than the merge kernel)
     a.fused = (mode == 1 || (mode == 0 && !long_lists && a.cols <= 8)) && n_pairs <= KV_DECODE_SYNC_WORDS &&
               a.n_waves < (1 << 16);
-    // Weights of the XCDs.  Under this kernel's load the odd-numbered XCDs stream slower than the
-    // even-numbered ones (their wavefronts end 8-13 % later on every workload measured), so
-    // `skew` / 1024 of an even share is moved from each odd to each even one.  The workgroup ->
-    // XCD rule only holds for whole rounds of eight workgroups; otherwise all weigh the same.
+    // Weights of the XCDs.  Workgroup L runs on XCD L mod 8 (read back from the hardware's XCC_ID by
+    // kv_probe_read_placed), and the XCDs do not stream equally fast: with equal shares the
+    // wavefronts of the odd-numbered ones end later on average (a plain read of equal contiguous
+    // shares takes them 2-3 % longer; in this kernel's time stamps the gap was larger).  `skew` / 1024
+    // of an even share is therefore moved from each odd to each even one, which shortens the calls
+    // measured by 1.5-2 %.  The workgroup -> XCD rule only holds for whole rounds of eight workgroups;
+    // otherwise all weigh the same.
     {
         int64_t skew = kv_option_xcd_skew();
         if (skew < 0) skew = kDefaultXcdSkew;

@@ -99,3 +99,47 @@ extern "C" int kv_probe_copy(void* dst, const void* src, size_t bytes, int n_wor
                        (hipStream_t)hip_stream, (const kv_u32x4*)src, (kv_u32x4*)dst, bytes / 16);
     return kv_record_hip_error(hipGetLastError(), "kv_probe_copy launch");
 }
+
+// Placement probe: workgroup g streams the g-th of gridDim.x equal contiguous shares (each of its
+// four wavefronts a quarter, 16 KiB per wavefront per trip) and records which XCD it ran on and
+// when it started and ended.
+__global__ __launch_bounds__(kProbeThreads) void probe_read_placed_kernel(const kv_u32x4* __restrict__ src,
+                                                                          size_t vecs_per_wave, int64_t* records,
+                                                                          uint32_t* sink)
+{
+    const long long t0 = (long long)__builtin_amdgcn_s_memrealtime();
+    const int lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6);
+    const kv_u32x4* p = src + wave * vecs_per_wave;
+    kv_u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = lane;
+    for (; i + 15 * 64 < vecs_per_wave; i += 16 * 64) {
+        kv_u32x4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(p + i + u * 64);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc ^= v[u];
+    }
+    for (; i < vecs_per_wave; i += 64) acc ^= __builtin_nontemporal_load(p + i);
+    const uint32_t f = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (f == 0x9e3779b9u && sink) sink[0] = f;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        // hardware register 20 (XCC_ID), bits 3:0: the XCD this workgroup runs on
+        const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+        records[(size_t)blockIdx.x * 3] = (int64_t)xcc;
+        records[(size_t)blockIdx.x * 3 + 1] = t0;
+        records[(size_t)blockIdx.x * 3 + 2] = (long long)__builtin_amdgcn_s_memrealtime();
+    }
+}
+
+extern "C" int kv_probe_read_placed(const void* src, size_t bytes, int64_t* records, void* sink,
+                                    int n_workgroups, void* hip_stream)
+{
+    if (!src || !records || n_workgroups <= 0) return KV_ERR_INVALID_ARG;
+    const size_t waves = (size_t)n_workgroups * (kProbeThreads / 64);
+    const size_t vecs_per_wave = bytes / 16 / waves;
+    hipLaunchKernelGGL(probe_read_placed_kernel, dim3((unsigned)n_workgroups), dim3(kProbeThreads), 0,
+                       (hipStream_t)hip_stream, (const kv_u32x4*)src, vecs_per_wave, records, (uint32_t*)sink);
+    return kv_record_hip_error(hipGetLastError(), "kv_probe_read_placed launch");
+}
