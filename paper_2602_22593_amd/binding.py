@@ -176,7 +176,7 @@ def _workspace(device, nbytes: int, stream=None, kind: str = "scratch") -> torch
     key = (device.index, stream.cuda_stream, kind)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        # zero-filled: the decode kernels expect their arrival words (the first bytes) to start at zero
+        # zero-filled: the kernels expect their arrival words (the first bytes) to start at zero
         with torch.cuda.stream(stream):
             ws = torch.zeros(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
         _workspaces[key] = ws

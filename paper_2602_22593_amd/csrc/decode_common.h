@@ -61,4 +61,23 @@ __device__ __forceinline__ void combine(float& m, float& l, float (&a)[N], float
     m = mn;
 }
 
+// Data that travels between workgroups which may run on different XCDs, each with its own L2, is
+// written and read with relaxed device-scope atomic accesses of 64 bits, which the hardware serves
+// at the device's point of coherence (write-through stores, loads that bypass the local caches).
+// Ordering comes from waiting for the stores' acknowledgement (s_waitcnt vmcnt(0)) before an arrival
+// counter is touched, not from cache-wide fences.
+__device__ __forceinline__ void st_coherent2(float* p, float x, float y)
+{
+    const unsigned long long bits =
+        (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x2 ld_coherent2(const float* p)
+{
+    const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return f32x2{__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32))};
+}
+
 }  // namespace kvdec

@@ -412,20 +412,6 @@ __device__ __forceinline__ splitter split_prologue(const kv_streamk_args& a, int
 // at the device's point of coherence (write-through stores, loads that bypass the local caches);
 // ordering comes from waiting for the stores' acknowledgement before the arrival word is touched,
 // not from cache-wide fences.
-__device__ __forceinline__ void st_coherent2(float* p, float x, float y)
-{
-    const unsigned long long bits =
-        (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ f32x2 ld_coherent2(const float* p)
-{
-    const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
-                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return f32x2{__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32))};
-}
-
 // Lane (r, quad), r < cols, holds o[j][i] = O[row r][32 quad + 8 i + j] of the piece; m and l are the
 // row's maximum and denominator (the same in the four lanes of a row).  The rows go through the
 // wavefront's LDS buffer (8 KiB, free between tiles) so that one store instruction writes one whole

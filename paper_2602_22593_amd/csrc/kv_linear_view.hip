@@ -6,38 +6,39 @@
 // copied: the kernel addresses the full matrix with its own leading dimension.
 //
 // Shaped for decode batches (M up to a few hundred rows): the weight slice is streamed from HBM
-// once per 64 batch rows and is the only traffic that matters; x is small, but every weight row
-// needs all of it, so the workgroup shares it through LDS.  A workgroup of four wavefronts owns
-// 16 RB logical weight rows (RB = 1 or 2 blocks of 16) x 64 batch rows over the whole input
-// dimension (or its share of it), walked in slabs of 128 input features.  With RB row blocks the
-// 4 / RB wavefronts of a row block each take a part of every slab and add up through LDS once, at
-// the end, so no output tile is cut over workgroups unless the launch would otherwise be too small
-// to fill the chip: partial tiles cost as much traffic as the weights they stand for at these
-// batch sizes.  RB is the largest that still gives about two hundred workgroups.
+// once per 64 batch rows and is the only HBM traffic that matters.  What limits such a product on
+// this chip is not HBM but the path from L2 into a compute unit (measured here: about 18 bytes per
+// clock per compute unit for 16-byte loads that hit L2): every weight row needs all of x, so a
+// workgroup that walks the whole input dimension pulls x (M x K, far more than fits in registers or
+// LDS) through that path again and again, two to four times the bytes of the weights it streams.
 //
-// The walk is one continuous stream.  A load instruction fetches four rows, 256 contiguous bytes of
-// each (64-byte pieces of a row per instruction, as the operand arrangement would ask for, halve the
-// rate at which HBM delivers the weights), into a ring of registers four slabs deep; a slab's
-// requests are issued three slabs before it is used, and every round issues exactly one slab's
-// worth, rounds past the end included (those ask for 16 bytes and multiply by zero): with nothing
-// conditional about the loads the compiler's count of outstanding requests is exact, and a round
-// waits for its own slab only.  Arrived rows go into one of two LDS buffers, XOR-swizzled so that
-// the row-wise writes and the operand-wise reads are both free of bank conflicts; one barrier per
-// slab (a bare one: the fences of __syncthreads() would drain the request queue); the matrix
-// instructions of a slab run in the round after, while the next slab's operand reads are under way.
-// Every workgroup starts its walk at another slab, so that the workgroups do not ask for the same
-// column range of all rows at the same time.
+// So x stays put.  The input dimension is cut into slices of at most 8 slabs of 128 input features,
+// and a workgroup owns one slice x 64 batch rows x NB blocks of 16 logical weight rows.  Each of its
+// four wavefronts takes two slabs of the slice (w and w + 4) and loads its 64 x 256 piece of x ONCE,
+// straight into the arrangement of the matrix instruction's B operand, where it stays for the whole
+// kernel (128 registers).  Then the wavefront walks the NB row blocks: a block's 16 rows x 2 slabs
+// are requested four rows of 256 contiguous bytes per load instruction (64-byte pieces of a row per
+// instruction, as the operand arrangement would ask for, halve the rate at which HBM delivers the
+// weights), two row blocks ahead of the arithmetic, pass through a private LDS area of the wavefront
+// (XOR-swizzled so that the row-wise writes and the operand-wise reads are free of bank conflicts)
+// and come back as A operands:
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
-// with 16x16x32 bf16 MFMA, fp32 accumulation, one rounding to bf16 at the end.  When the input
-// dimension is cut over `splits` workgroups (small slices only), each leaves an fp32 partial tile in
-// the workspace and a second, small kernel adds the splits in a fixed order (deterministic).
+// with 16x16x32 bf16 MFMA, fp32 accumulation.  The walk is straight-line code (NB is a template
+// parameter): the compiler's count of outstanding requests is then exact and a row block waits for
+// its own rows only.  No workgroup barrier until the end, where the four wavefronts add their
+// accumulators through LDS.  With one slice the sums are rounded to bf16 and stored; with several,
+// each workgroup leaves an fp32 partial tile in the workspace and a second, small kernel adds the
+// slices in a fixed order (deterministic) and rounds once.  NB is chosen so that the launch has at
+// least one workgroup per compute unit.
 //
-// Where the time goes (measured by replacing the requests by idle ones): on the 8B projections at
-// M = 64 the kernel takes 16-19 us with no memory traffic at all.  A round costs a workgroup about
-// 0.45 us: 24 KiB written to and 40 KiB read from LDS, eight matrix instructions per wavefront, and
-// the barrier keeps the four wavefronts of a compute unit in the same phase, so LDS and matrix
-// pipe take turns instead of overlapping.  The weight stream itself is not the limit yet.
+// Where the time goes (time stamps inside the kernel, fused QKV weight of 6144 x 4096 at M = 64,
+// 16.8 us for the first kernel): the first weight rows and x are in the registers 5.9 us after the
+// first wavefront starts (three dependent cold accesses: kernel arguments, first rows from HBM, x),
+// the six row blocks are done at 10.5 us (the 50 MB stream averages 5 TB/s from the first request
+// on), the accumulators are added and stored at 12.3 us; the rest is the launch and the write-back
+// of the partial tiles at the kernel's end.  The second kernel adds 3.7 us.
 #include <string.h>
+#include <hip/hip_ext.h>
 
 #include "decode_common.h"
 
@@ -46,6 +47,7 @@ using namespace kvdec;
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
 constexpr int kColBlocks = 4;   // 16-row blocks of x per workgroup
 constexpr int kSlab = 128;      // input features per slab
 
@@ -61,265 +63,260 @@ struct linear_args {
     int32_t n_seg;
     int64_t seg_start[3];   // first stored row of each segment
     int32_t seg_first[4];   // first logical row of each segment; seg_first[n_seg] = Nl
-    int32_t splits;         // workgroups sharing the input dimension of one output tile
-    float* part;            // [splits][M][Nl] fp32 when splits > 1
+    int32_t splits;         // slices of the input dimension
+    int32_t slice_slabs;    // 128-wide slabs per slice (at most 8)
+    float* part;            // [splits][workgroup tile][NB * 4 tiles][64 lanes] f32x4 when splits > 1
 };
 
-// s_waitcnt vmcnt(N), N <= 63, leaving the other counters alone
-template <int N>
-__device__ __forceinline__ void wait_vm()
+// sum[i] = y[m0 + 16 cb + r][16 (blk0 + b) + 4 quad + i] for tile (b, cb) = (tile / 4, tile % 4) of a
+// workgroup: rounded to bf16 and stored
+template <int NB>
+__device__ __forceinline__ void store_tile(const linear_args& p, f32x4 sum, int tile, int m0, int blk0, int n_blocks,
+                                           int r, int quad)
 {
-    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+    const int b = tile / kColBlocks, cb = tile % kColBlocks;
+    const int m = m0 + 16 * cb + r;
+    if (m >= p.M || blk0 + b >= n_blocks) return;
+    uint2 pk;
+    pk.x = pack_bf16x2(sum[0], sum[1]);
+    pk.y = pack_bf16x2(sum[2], sum[3]);
+    *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + (16 * (blk0 + b) + 4 * quad)) = pk;
 }
-// wait until at most `slabs` slabs of OPS loads each are outstanding
-template <int OPS>
-__device__ __forceinline__ void wait_slabs(int slabs)
+
+// The partial tiles of all slices of one workgroup tile, added in slice order and stored.  Wavefront w takes tiles w NB .. w NB + NB - 1.
+template <int NB>
+__device__ __forceinline__ void add_slices(const linear_args& p, int64_t wg_tiles, int64_t wg_tile, int m0, int blk0,
+                                           int n_blocks, int wave, int lane)
 {
-    switch (slabs) {
-        case 0: wait_vm<0>(); break;
-        case 1: wait_vm<OPS>(); break;
-        case 2: wait_vm<2 * OPS>(); break;
-        case 3: wait_vm<3 * OPS>(); break;
-        case 4: wait_vm<4 * OPS>(); break;
-        case 5: wait_vm<5 * OPS>(); break;
-        case 6: wait_vm<6 * OPS>(); break;
-        default: wait_vm<(7 * OPS > 63 ? 63 : 7 * OPS)>(); break;
+    const int r = lane & 15, quad = lane >> 4;
+    const int64_t slice_step = wg_tiles * (NB * kColBlocks) * 256;   // floats between two slices
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int tile = wave * NB + t;
+        const float* src = p.part + ((wg_tile * (NB * kColBlocks) + tile) * 64 + lane) * 4;
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int z0 = 0; z0 < p.splits; z0 += 4) {   // four slices requested at a time
+            f32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)min(z0 + j, p.splits - 1) * slice_step);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (z0 + j < p.splits) sum += v[j];
+        }
+        store_tile<NB>(p, sum, tile, m0, blk0, n_blocks, r, quad);
     }
 }
 
-// Workgroup barrier without the memory fences of __syncthreads(): those would make every wavefront
-// wait for ALL its outstanding loads, the seven slabs in flight included.  What has to be complete
-// at this barrier is stated by the caller's own vmcnt wait (the slab about to be consumed) and by the
-// LDS reads of the previous slab having returned to the matrix instructions that used them.
-__device__ __forceinline__ void stream_barrier()
+template <int NB>
+__global__ __launch_bounds__(kThreads, 1) void linear_slice_kernel(linear_args p)
 {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-template <int RB>
-__global__ __launch_bounds__(kThreads, 2) void linear_stream_kernel(linear_args p)
-{
-    constexpr int KP = 4 / RB;        // wavefronts sharing a row block, each a part of every slab
-    constexpr int KK = 4 / KP;        // 32-wide steps of a slab per wavefront
-    constexpr int NR = 4;             // slabs in the register ring: NR - 1 requested ahead (even)
-    // A slab in LDS: rows of 16 16-byte pieces (x: 64 batch rows; w: the workgroup's 16 RB weight
-    // rows), piece q of row t kept at position q ^ (t % 16): the row-wise staging writes and the MFMA
-    // operand reads (lane (r, quad): row r, piece 4 kk + quad) both touch every bank once per 16 lanes.
-    __shared__ kv_u32x4 s_x[2][1024];
-    __shared__ kv_u32x4 s_w[2][256 * RB];
+    constexpr int NR = 3;             // row blocks requested ahead
+    constexpr int kStagePieces = 2 * 256;                       // per wavefront: 2 slabs x 16 rows x 16 pieces
+    constexpr int kRedPieces = kWaves * NB * kColBlocks * 64;   // all accumulators, one f32x4 per lane each
+    constexpr int kLdsPieces = kWaves * kStagePieces > kRedPieces ? kWaves * kStagePieces : kRedPieces;
+    __shared__ kv_u32x4 s_mem[kLdsPieces];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, quad = lane >> 4;
-    const int rb = wave % RB, kp = wave / RB;
-    const int m0 = blockIdx.x * (16 * kColBlocks);
-    const int n0 = blockIdx.y * (16 * RB);
-
-    // the rows of this workgroup lie in one segment (segment sizes are multiples of 64)
-    int seg = 0;
-    while (seg + 1 < p.n_seg && n0 >= p.seg_first[seg + 1]) ++seg;
-    const int64_t phys0 = p.seg_start[seg] + (n0 - p.seg_first[seg]);
-
-    // staging: a load instruction covers four rows, 256 contiguous bytes of each: lane = 16 g + pos
-    // fetches piece pos of row 4 u + g.  x: wavefront w stages batch rows 16 w .. 16 w + 15 (rows past M
-    // repeat the last one); weights: wavefront w stages rows 4 (RB w + i) .. + 3, i < RB
     const int g = lane >> 4, pos = lane & 15;
-    const char* xsrc[4];
-    int xdst[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int row = 16 * wave + 4 * u + g;
-        xsrc[u] = reinterpret_cast<const char*>(p.x + (int64_t)min(m0 + row, p.M - 1) * p.ldx) + (pos << 4);
-        xdst[u] = row * 16 + (pos ^ (row & 15));
-    }
-    const char* wsrc[RB];
-    int wdst[RB];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) {
-        const int row = 4 * (RB * wave + i) + g;
-        wsrc[i] = reinterpret_cast<const char*>(p.w + (phys0 + row) * p.ldw + p.col_start) + (pos << 4);
-        wdst[i] = row * 16 + (pos ^ (row & 15));
-    }
+    const int blk0 = blockIdx.x * NB;                 // first 16-row block of this workgroup
+    const int m0 = blockIdx.y * (16 * kColBlocks);
+    kv_u32x4* stage = s_mem + wave * kStagePieces;
 
-    // this workgroup's slabs: [first, first + n)
+    // this workgroup's slabs: [first, first + n); this wavefront's: first + w and first + w + 4
     const int total = p.Kl / kSlab;
-    const int per_split = (total + p.splits - 1) / p.splits;
-    const int first = (int)blockIdx.z * per_split;
-    const int n = min(total, first + per_split) - first;
-
-    // Every workgroup starts its walk at another slab and wraps around, so that at any moment the
-    // workgroups ask for different column ranges: rows are a power of two apart, and the same columns
-    // of all rows share a few memory channels.
-    const int rot = (int)((blockIdx.y * 5u + blockIdx.x * 3u) % (unsigned)n);
-    // The walk is written without a single conditional load: every round requests exactly one slab
-    // (rounds past the end request 16 bytes of x, the same for all lanes, and multiply by zero).  The
-    // compiler then knows in every round that the registers it is about to use were requested NR - 1
-    // requests ago and waits for exactly those; with requests that may or may not have been issued it
-    // has to assume the worst and drains the whole queue.
-    kv_u32x4 x_reg[NR][4], w_reg[NR][RB];
-    auto issue = [&](int j, int slot) {   // loads of the j-th slab of this workgroup's walk into ring slot `slot`
-        // (address arithmetic instead of a choice between two pointers: a choice on a condition that
-        // is the same for the whole wavefront is compiled into two paths with a load and a wait each)
-        const int64_t keep = j < n ? (int64_t)-1 : 0;
-        int jr = j + rot;
-        if (jr >= n) jr -= n;
-        const int64_t off = (int64_t)(first + jr) * (kSlab * 2);
-        const char* idle = reinterpret_cast<const char*>(p.x);
+    const int first = (int)blockIdx.z * p.slice_slabs;
+    const int n = min(total, first + p.slice_slabs) - first;
+    bool have[2];
+    int64_t koff[2];   // byte offset of the slab inside a row; a missing slab reads the slice's first one
 #pragma unroll
-        for (int i = 0; i < RB; ++i)
-            w_reg[slot][i] = __builtin_nontemporal_load(
-                reinterpret_cast<const kv_u32x4*>(idle + (((wsrc[i] + off) - idle) & keep)));
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            x_reg[slot][u] = *reinterpret_cast<const kv_u32x4*>(idle + (((xsrc[u] + off) - idle) & keep));
-    };
-
-    f32x4 acc[kColBlocks];
-#pragma unroll
-    for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Round j: slab j goes from this wavefront's registers into LDS buffer j % 2 and its ring slot
-    // takes the next request; after the barrier the operands of slab j are read from LDS and, while
-    // those reads are under way, the matrix instructions of slab j - 1 run on the operands read in the
-    // round before: with one wavefront per SIMD nothing else would hide the LDS latency.
-    kv_u32x4 a_op[2][KK], b_op[2][KK][kColBlocks];
-    auto read_operands = [&](int buf, int which, bool real) {
-        const kv_u32x4* xb = s_x[buf];
-        const kv_u32x4* wrow = s_w[buf] + (16 * rb + r) * 16;
-#pragma unroll
-        for (int t = 0; t < KK; ++t) {
-            const int q = 4 * (kp * KK + t) + quad;
-            a_op[which][t] = wrow[q ^ r];
-            if (!real) a_op[which][t] = kv_u32x4{0u, 0u, 0u, 0u};   // a round past the end adds nothing
-#pragma unroll
-            for (int cb = 0; cb < kColBlocks; ++cb) b_op[which][t][cb] = xb[(16 * cb + r) * 16 + (q ^ r)];
-        }
-    };
-    auto multiply = [&](int which) {
-#pragma unroll
-        for (int t = 0; t < KK; ++t)
-#pragma unroll
-            for (int cb = 0; cb < kColBlocks; ++cb)
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_op[which][t]),
-                                                                  as_bf16x8(b_op[which][t][cb]), acc[cb], 0, 0, 0);
-    };
-#pragma unroll
-    for (int t = 0; t < KK; ++t) {
-        a_op[1][t] = kv_u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int cb = 0; cb < kColBlocks; ++cb) b_op[1][t][cb] = kv_u32x4{0u, 0u, 0u, 0u};
+    for (int t = 0; t < 2; ++t) {
+        have[t] = wave + kWaves * t < n;
+        koff[t] = (int64_t)(first + (have[t] ? wave + kWaves * t : 0)) * (kSlab * 2);
     }
 
+    // Addresses are a base that is the same for the whole wavefront (scalar registers) plus one
+    // 32-bit offset per lane.  One load instruction covers four rows, 256 contiguous bytes of each:
+    // lane 16 g + pos fetches piece pos of row 4 i + g (whole cache lines: the arrangement the matrix
+    // instruction wants, 64 bytes of each of 16 rows, costs the load path twice as long per byte).
+    // A block past the last row, or a missing slab, asks for bytes of x instead (there and cached)
+    // and multiplies by zero; the choice is made by arithmetic on the base and the lane offset, never
+    // between two loads (a choice between loads is compiled into two paths with a wait each).
+    const char* idle = reinterpret_cast<const char*>(p.x);
+    const uint32_t idle_lane = (uint32_t)(pos << 4);
+    const uint32_t wlane = (uint32_t)(g * p.ldw * 2 + (pos << 4));
+    const int64_t wstep = 4 * p.ldw * 2;
+    const int n_blocks = p.Nl >> 4;
+    kv_u32x4 w_reg[NR][2][4];
+    auto issue = [&](int b, int slot) {
+        const int blk = blk0 + b;
+        const int row = min(blk, n_blocks - 1) << 4;     // (a block never straddles two segments)
+        int seg = 0;
+        seg += (p.n_seg > 1 && row >= p.seg_first[1]);
+        seg += (p.n_seg > 2 && row >= p.seg_first[2]);
+        const int64_t phys = p.seg_start[seg] + (row - p.seg_first[seg]);
+        const char* rows = reinterpret_cast<const char*>(p.w + phys * p.ldw + p.col_start);
 #pragma unroll
-    for (int j = 0; j < NR - 1; ++j) issue(j, j);
-    for (int j0 = 0; j0 < n; j0 += NR) {
+        for (int t = 0; t < 2; ++t) {
+            const int64_t keep = -(int64_t)(blk < n_blocks && have[t]);
+            const uint32_t lane_off = idle_lane + ((wlane - idle_lane) & (uint32_t)keep);
 #pragma unroll
-        for (int jj = 0; jj < NR; ++jj) {
-            const int j = j0 + jj;
-            kv_u32x4* xb = s_x[jj & 1];
-            kv_u32x4* wb = s_w[jj & 1];
+            for (int i = 0; i < 4; ++i) {
+                const char* base = idle + (((rows + koff[t] + i * wstep) - idle) & keep);
+                w_reg[slot][t][i] = __builtin_nontemporal_load(reinterpret_cast<const kv_u32x4*>(base + lane_off));
+            }
+        }
+    };
+    // the first weight rows are requested before x: they come from HBM, x mostly from L2
 #pragma unroll
-            for (int i = 0; i < RB; ++i) wb[wdst[i]] = w_reg[jj][i];
+    for (int b = 0; b < NR && b < NB; ++b) issue(b, b);
+
+    // x, once: fetched like weight rows (16 batch rows x 1 slab at a time), passed through the private
+    // LDS area and kept as B operands: x_reg[t][kk][cb] = the 16 bytes of batch row 16 cb + r, 32-wide
+    // step kk of slab t, that lane (r, quad) contributes (rows past M repeat the last one)
+    kv_u32x4 x_reg[2][4][kColBlocks];
+    {
+        const char* xbase = reinterpret_cast<const char*>(p.x);
+        kv_u32x4 raw[2][kColBlocks][4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) xb[xdst[u]] = x_reg[jj][u];
-            issue(j + NR - 1, (jj + NR - 1) % NR);
-            // this wavefront's pieces are written, and its operand reads of the round before (from the
-            // other buffer, which the next round overwrites) have returned
-            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-            stream_barrier();
-            read_operands(jj & 1, jj & 1, j < n);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply((jj + 1) & 1);
+        for (int cb = 0; cb < kColBlocks; ++cb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t xlane = (uint32_t)(min(m0 + 16 * cb + 4 * i + g, p.M - 1) * p.ldx * 2 + (pos << 4));
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    raw[t][cb][i] = *reinterpret_cast<const kv_u32x4*>(xbase + koff[t] + xlane);
+            }
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = 4 * i + g;
+                    stage[t * 256 + row * 16 + (pos ^ row)] = raw[t][cb][i];
+                }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) x_reg[t][kk][cb] = stage[t * 256 + r * 16 + ((4 * kk + quad) ^ r)];
+            __builtin_amdgcn_wave_barrier();
         }
     }
-    multiply((NR - 1) & 1);   // the last round's slab (NR is even: its operands are in set 1)
 
-    // the wavefronts of a row block add up (buffers are free once everybody has left the loop)
-    if (KP > 1) {
-        __syncthreads();
-        f32x4* red = reinterpret_cast<f32x4*>(&s_x[0][0]);   // [wave][cb][lane]
-        if (kp > 0) {
+    f32x4 acc[NB][kColBlocks];
 #pragma unroll
-            for (int cb = 0; cb < kColBlocks; ++cb) red[(wave * kColBlocks + cb) * 64 + lane] = acc[cb];
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb) acc[b][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int slot = b % NR;
+        // registers -> private LDS area (piece q of row t at position q ^ t) -> A operands
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 4 * i + g;
+                stage[t * 256 + row * 16 + (pos ^ row)] = w_reg[slot][t][i];
+            }
+        if (b + NR < NB) issue(b + NR, slot);
+        // (LDS serves a wavefront's requests in order: the reads below see these writes, and the next
+        // block's writes come after these reads)
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bool real = have[t] && blk0 + b < n_blocks;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                kv_u32x4 a_op = stage[t * 256 + r * 16 + ((4 * kk + quad) ^ r)];
+                if (!real) a_op = kv_u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int cb = 0; cb < kColBlocks; ++cb)
+                    acc[b][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a_op), as_bf16x8(x_reg[t][kk][cb]),
+                                                                        acc[b][cb], 0, 0, 0);
+            }
         }
-        __syncthreads();
-        if (kp > 0) return;
-#pragma unroll
-        for (int k = 1; k < KP; ++k)
-#pragma unroll
-            for (int cb = 0; cb < kColBlocks; ++cb) acc[cb] += red[((k * RB + rb) * kColBlocks + cb) * 64 + lane];
     }
 
-    // acc[cb][i] = y[m0 + 16 cb + r][n0 + 16 rb + 4 quad + i]
+    // the four wavefronts add up: each writes its accumulators, then sums NB of the 4 NB tiles
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(s_mem);   // [wave][b][cb][lane]
 #pragma unroll
-    for (int cb = 0; cb < kColBlocks; ++cb) {
-        const int m = m0 + 16 * cb + r;
-        if (m >= p.M) continue;
-        const int nn = n0 + 16 * rb + 4 * quad;
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks; ++cb) red[((wave * NB + b) * kColBlocks + cb) * 64 + lane] = acc[b][cb];
+    __syncthreads();
+    const int64_t wg_tiles = (int64_t)gridDim.x * gridDim.y;
+    const int64_t wg_tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int tile = wave * NB + t;           // of the 4 NB (b, cb) tiles
+        const int b = tile / kColBlocks, cb = tile % kColBlocks;
+        f32x4 sum = red[((0 * NB + b) * kColBlocks + cb) * 64 + lane];
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) sum += red[((k * NB + b) * kColBlocks + cb) * 64 + lane];
         if (p.splits > 1) {
-            *reinterpret_cast<f32x4*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.Nl + nn) = acc[cb];
+            // partial tile, kept lane for lane as it lies in the registers: 1 KiB contiguous per store
+            *reinterpret_cast<f32x4*>(
+                p.part + ((((int64_t)blockIdx.z * wg_tiles + wg_tile) * (NB * kColBlocks) + tile) * 64 + lane) * 4) = sum;
         } else {
-            uint2 pk;
-            pk.x = pack_bf16x2(acc[cb][0], acc[cb][1]);
-            pk.y = pack_bf16x2(acc[cb][2], acc[cb][3]);
-            *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + nn) = pk;
+            store_tile<NB>(p, sum, tile, m0, blk0, n_blocks, r, quad);
         }
     }
 }
 
-// y[m][n .. n + 4) = bf16(sum over splits of part[z][m][n .. n + 4)), splits added in order
-__global__ __launch_bounds__(256) void linear_reduce_kernel(linear_args p)
+// The second kernel of a launch with several slices: one workgroup per workgroup tile adds them.
+// (Letting the last slice to arrive do this inside the first kernel was measured and gains nothing:
+// partials that cross XCDs inside a kernel need write-through stores, their acknowledgement, an
+// arrival counter and cache-bypassing loads, a chain as long as the second launch.)
+template <int NB>
+__global__ __launch_bounds__(kThreads) void linear_add_kernel(linear_args p)
 {
-    const int64_t quads = (int64_t)p.M * (p.Nl / 4);
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= quads) return;
-    const int64_t m = i / (p.Nl / 4), n = (i - m * (p.Nl / 4)) * 4;
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    // four partial tiles requested at a time, then added in order (one memory round trip per four
-    // splits instead of one per split)
-    const float* src = p.part + m * p.Nl + n;
-    const int64_t step = (int64_t)p.M * p.Nl;
-    for (int z0 = 0; z0 < p.splits; z0 += 4) {
-        f32x4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            v[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)min(z0 + j, p.splits - 1) * step);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (z0 + j < p.splits) s += v[j];
-    }
-    uint2 pk;
-    pk.x = pack_bf16x2(s[0], s[1]);
-    pk.y = pack_bf16x2(s[2], s[3]);
-    *reinterpret_cast<uint2*>(p.y + m * p.ldy + n) = pk;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    add_slices<NB>(p, (int64_t)gridDim.x * gridDim.y, (int64_t)blockIdx.y * gridDim.x + blockIdx.x,
+                   blockIdx.y * (16 * kColBlocks), blockIdx.x * NB, p.Nl >> 4, wave, lane);
 }
 
-// Row blocks per workgroup and workgroups sharing the input dimension of one output tile.
-// Whole tiles per workgroup wherever that gives about two hundred workgroups (the launch has to
-// keep enough bytes in flight, not to occupy every compute unit); the input dimension is cut only
-// for slices too small for that, and then into as few parts as fill half the chip.
+// Slices of the input dimension and row blocks per workgroup.  A slice is what a workgroup can keep
+// of x in registers: 8 slabs; NB is the largest of 8, 6, 4, 3, 2, 1 that still gives one workgroup
+// per compute unit (more rows per workgroup use the resident piece of x for longer).
+constexpr int kSliceSlabs = 2 * kWaves;
 struct linear_cfg {
-    int rb, splits;
+    int nb, splits, slice_slabs;
 };
 linear_cfg pick_cfg(int64_t m_tiles, int64_t n_l, int total_slabs)
 {
-    linear_cfg c = {1, 1};
-    for (int rb = 2; rb >= 1; rb >>= 1) {
-        c.rb = rb;
-        if (m_tiles * (n_l / (16 * rb)) >= 192) break;
+    linear_cfg c;
+    c.slice_slabs = total_slabs < kSliceSlabs ? total_slabs : kSliceSlabs;
+    const int64_t forced = kv_option_linear_splits();   // test hook: at least this many slices
+    if (forced > 0) {
+        const int per = (int)((total_slabs + forced - 1) / forced);
+        c.slice_slabs = per < 1 ? 1 : per > kSliceSlabs ? kSliceSlabs : per;
     }
-    const int64_t tiles = m_tiles * (n_l / (16 * c.rb));
-    int s = 1;
-    while (s < 16 && s < total_slabs && tiles * s < 128) ++s;
-    const int64_t forced = kv_option_linear_splits();
-    if (forced > 0) s = (int)forced;
-    s = s > 16 ? 16 : s;
-    s = s > total_slabs ? total_slabs : s;
-    c.splits = s < 1 ? 1 : s;
+    c.splits = (total_slabs + c.slice_slabs - 1) / c.slice_slabs;
+    const int64_t blocks = n_l / 16;
+    static const int kNb[] = {8, 6, 4, 3, 2, 1};
+    c.nb = 1;
+    for (int nb : kNb) {
+        if (m_tiles * ((blocks + nb - 1) / nb) * c.splits >= 256) {
+            c.nb = nb;
+            break;
+        }
+    }
     return c;
+}
+
+// Workspace of a launch with several slices: one padded fp32 tile per slice and workgroup tile.
+size_t part_bytes(const linear_cfg& c, int64_t m_tiles, int64_t n_l)
+{
+    if (c.splits <= 1) return 0;
+    const int64_t n_tiles = (n_l / 16 + c.nb - 1) / c.nb;
+    return (size_t)c.splits * m_tiles * n_tiles * c.nb * kColBlocks * 1024;
 }
 
 int64_t view_rows(const kv_weight_view* view)
@@ -337,8 +334,8 @@ extern "C" size_t kv_linear_view_workspace_bytes(const kv_weight_view* view, int
     const int64_t n_l = view_rows(view);
     if (n_l <= 0) return 0;
     const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
-    const int splits = pick_cfg(m_tiles, n_l, (int)(view->col_count / kSlab)).splits;
-    return splits > 1 ? (size_t)splits * M * n_l * 4 : 0;
+    const linear_cfg cfg = pick_cfg(m_tiles, n_l, (int)(view->col_count / kSlab));
+    return part_bytes(cfg, m_tiles, n_l);
 }
 
 extern "C" int kv_weight_view_make(int dim, int r, int m, int64_t n_rows, int64_t n_cols, kv_weight_view* out)
@@ -427,24 +424,48 @@ extern "C" int kv_linear_view(const void* x, int64_t ldx, const void* w_full, in
     for (int i = view->n_segments; i < 4; ++i) p.seg_first[i] = first;
     const int64_t m_tiles = ((int64_t)M + 16 * kColBlocks - 1) / (16 * kColBlocks);
     const linear_cfg cfg = pick_cfg(m_tiles, n_l, p.Kl / kSlab);
-    const int64_t n_tiles = n_l / (16 * cfg.rb);
-    if (m_tiles > 0x7fffffff || n_tiles > 65535) return KV_ERR_UNSUPPORTED;
+    const int64_t n_tiles = (n_l / 16 + cfg.nb - 1) / cfg.nb;
+    // (per-lane offsets are 32 bits wide)
+    if (n_tiles > 0x7fffffff || m_tiles > 65535 || (int64_t)M * ldx >= (1ll << 31) || ldw >= (1ll << 28))
+        return KV_ERR_UNSUPPORTED;
     p.splits = cfg.splits;
+    p.slice_slabs = cfg.slice_slabs;
     p.part = (float*)workspace;
     if (p.splits > 1) {
         if (!workspace || ((uintptr_t)workspace & 15)) return KV_ERR_INVALID_ARG;
-        if (workspace_bytes < (size_t)p.splits * M * n_l * 4) return KV_ERR_WORKSPACE;
+        if (workspace_bytes < part_bytes(cfg, m_tiles, n_l)) return KV_ERR_WORKSPACE;
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    const int slot = kv_prof_begin(KV_PROF_LINEAR, st);
-    const dim3 grid((unsigned)m_tiles, (unsigned)n_tiles, (unsigned)p.splits);
-    if (cfg.rb == 2) hipLaunchKernelGGL(linear_stream_kernel<2>, grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL(linear_stream_kernel<1>, grid, dim3(kThreads), 0, st, p);
-    if (p.splits > 1) {
-        const int64_t quads = (int64_t)M * (n_l / 4);
-        hipLaunchKernelGGL(linear_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p);
+    const dim3 grid((unsigned)n_tiles, (unsigned)m_tiles, (unsigned)p.splits);
+    // (while kv_profile is on, a single-kernel call is launched with events that take the kernel's own
+    // start and end times; with a second kernel the two share a bracket of recorded events)
+    hipEvent_t e0, e1;
+    const bool own_events = p.splits == 1 && kv_prof_kernel_events(KV_PROF_LINEAR, &e0, &e1);
+    const int slot = own_events ? -1 : kv_prof_begin(KV_PROF_LINEAR, st);
+    auto go = [&](auto kernel) {
+        if (own_events) hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, e0, e1, 0, p);
+        else hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, st, p);
+    };
+    switch (cfg.nb) {
+        case 8: go(linear_slice_kernel<8>); break;
+        case 6: go(linear_slice_kernel<6>); break;
+        case 4: go(linear_slice_kernel<4>); break;
+        case 3: go(linear_slice_kernel<3>); break;
+        case 2: go(linear_slice_kernel<2>); break;
+        default: go(linear_slice_kernel<1>); break;
     }
-    kv_prof_end(KV_PROF_LINEAR, slot, st);
+    if (p.splits > 1) {
+        const dim3 tiles((unsigned)n_tiles, (unsigned)m_tiles);
+        switch (cfg.nb) {
+            case 8: hipLaunchKernelGGL(linear_add_kernel<8>, tiles, dim3(kThreads), 0, st, p); break;
+            case 6: hipLaunchKernelGGL(linear_add_kernel<6>, tiles, dim3(kThreads), 0, st, p); break;
+            case 4: hipLaunchKernelGGL(linear_add_kernel<4>, tiles, dim3(kThreads), 0, st, p); break;
+            case 3: hipLaunchKernelGGL(linear_add_kernel<3>, tiles, dim3(kThreads), 0, st, p); break;
+            case 2: hipLaunchKernelGGL(linear_add_kernel<2>, tiles, dim3(kThreads), 0, st, p); break;
+            default: hipLaunchKernelGGL(linear_add_kernel<1>, tiles, dim3(kThreads), 0, st, p); break;
+        }
+    }
+    if (!own_events) kv_prof_end(KV_PROF_LINEAR, slot, st);
     return kv_record_hip_error(hipGetLastError(), "kv_linear_view launch");
 }
 

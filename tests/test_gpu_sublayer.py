@@ -119,8 +119,12 @@ def test_tp_ranks_reproduce_the_dp_engine():
             # reference maximum the bf16 probabilities are scaled by): a few bf16 ulps at most
             hql = HQ // m
             a_r, a_dp = bf16_bits_to_f64(attn_r), bf16_bits_to_f64(attn_dp[:, r * hql:(r + 1) * hql])
-            # (bf16 probabilities: 2^-9 relative per term of a sum of O(1) values, plus the output rounding)
-            assert (np.abs(a_r - a_dp) <= np.abs(a_dp) * 2.0 ** -6 + 4e-3).all(), (m, r, float(np.abs(a_r - a_dp).max()))
+            # Measured: TP2 ranks (the same kernel as DP) differ from DP in 1-2 of 12288 values, by
+            # 4e-6 at most; TP4 ranks (one head per wavefront) in about 30 % of the values by one
+            # bf16 ulp, in a few by two (largest difference 0.0078, largest excess over 2^-7 |x|
+            # 3.1e-3): the bf16 probabilities are rounded against different running maxima, 2^-9
+            # relative per term of a sum of O(1) values, before the output rounding.
+            assert (np.abs(a_r - a_dp) <= np.abs(a_dp) * 2.0 ** -7 + 4e-3).all(), (m, r, float(np.abs(a_r - a_dp).max()))
             total += bf16_bits_to_f64(y_r)
         # sum of the ranks' bf16 partials vs the DP engine's single bf16 result: m + 1 roundings apart
         want = bf16_bits_to_f64(y_dp)
