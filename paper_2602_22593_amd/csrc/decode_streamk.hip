@@ -1226,17 +1226,27 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     // to the common maximum and summed through LDS
     float mr = kNegInf, ll = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int w = w_first + slice; w <= w_last; w += nsl) {
-        const int64_t rec = (w + pair) * G + g;
-        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
-        const f32x4 part = *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4);
-        // (a wavefront that had no tiles left m = -inf, l = 0 and zeros: its weight comes out as 0)
-        const float mn = fmaxf(mr, ml.x);
-        const float ref = (mn == kNegInf) ? 0.f : mn;
-        const float c_old = fast_exp2(mr - ref), c_new = fast_exp2(ml.x - ref);
-        ll = ll * c_old + ml.y * c_new;
-        acc = acc * c_old + part * c_new;
-        mr = mn;
+    // (four pieces requested at a time: one memory round trip per four pieces, not one per piece)
+    for (int w0 = w_first + slice; w0 <= w_last; w0 += 4 * nsl) {
+        float2 ml[4];
+        f32x4 part[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t rec = (min(w0 + j * nsl, w_last) + pair) * G + g;
+            ml[j] = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
+            part[j] = *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (w0 + j * nsl > w_last) break;
+            // (a wavefront that had no tiles left m = -inf, l = 0 and zeros: its weight comes out as 0)
+            const float mn = fmaxf(mr, ml[j].x);
+            const float ref = (mn == kNegInf) ? 0.f : mn;
+            const float c_old = fast_exp2(mr - ref), c_new = fast_exp2(ml[j].x - ref);
+            ll = ll * c_old + ml[j].y * c_new;
+            acc = acc * c_old + part[j] * c_new;
+            mr = mn;
+        }
     }
     if (cg == 0) s_max[slice] = mr;
     __syncthreads();
