@@ -159,6 +159,10 @@ def main():
     ap.add_argument("--placement", action="store_true",
                     help="only run the placement probe (which XCD each workgroup index runs on, and how "
                          "fast each XCD streams its share of 256 MiB) and exit")
+    ap.add_argument("--extras-only", default=None, metavar="SECTION[:INDEX]",
+                    help="of the rows beyond the headline workload, run only this section of the output's "
+                         "'extras' (kv_repack, kv_repack_long, other_workloads, mixed_layout_decode, "
+                         "paged_prefill_attn, kv_linear_view), or only its INDEX-th case: for profiler runs")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
                     help="set a library option (kv_set_option) before measuring; may be repeated")
     args = ap.parse_args()
@@ -329,26 +333,35 @@ def main():
                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                  "frac": round(2 * moved / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}}
 
+        only_section, _, only_index = (args.extras_only or "").partition(":")
+
+        def want(section, index=None):
+            if not only_section:
+                return True
+            return section == only_section and (only_index == "" or index is None or int(only_index) == index)
+
         steps = max(50, args.steps // 2)
-        rw = wl.WORKLOADS["llama8b_tp_b128"]
-        rc = harness.build_repack_case(rw, (0, 1, 0), (1, 4, 0))
-        fwd = timed_repack(rc.forward, steps)
-        bwd = timed_repack(rc.backward, steps)
-        extras["kv_repack"] = {"workload": rw.name, "moved_bytes": rc.moved_bytes, "calls_timed": steps,
-                               "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd),
-                               "tp4_r0_to_dp": repack_row(rc.moved_bytes, *bwd)}
-        del rc
-        torch.cuda.empty_cache()
-        lw = wl.WORKLOADS["llama8b_tp4_longmix"]
-        rc = harness.build_repack_case(lw, (0, 1, 0), (1, 4, 0), np.array([131072, 131072], dtype=np.int32))
-        fwd = timed_repack(rc.forward, steps)
-        extras["kv_repack_long"] = {"workload": lw.name, "what": "the two 131072-token sequences, DP -> TP4 rank 0",
-                                    "moved_bytes": rc.moved_bytes, "calls_timed": steps,
-                                    "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd)}
-        del rc
-        torch.cuda.empty_cache()
+        if want("kv_repack"):
+            rw = wl.WORKLOADS["llama8b_tp_b128"]
+            rc = harness.build_repack_case(rw, (0, 1, 0), (1, 4, 0))
+            fwd = timed_repack(rc.forward, steps)
+            bwd = timed_repack(rc.backward, steps)
+            extras["kv_repack"] = {"workload": rw.name, "moved_bytes": rc.moved_bytes, "calls_timed": steps,
+                                   "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd),
+                                   "tp4_r0_to_dp": repack_row(rc.moved_bytes, *bwd)}
+            del rc
+            torch.cuda.empty_cache()
+        if want("kv_repack_long"):
+            lw = wl.WORKLOADS["llama8b_tp4_longmix"]
+            rc = harness.build_repack_case(lw, (0, 1, 0), (1, 4, 0), np.array([131072, 131072], dtype=np.int32))
+            fwd = timed_repack(rc.forward, steps)
+            extras["kv_repack_long"] = {"workload": lw.name, "what": "the two 131072-token sequences, DP -> TP4 rank 0",
+                                        "moved_bytes": rc.moved_bytes, "calls_timed": steps,
+                                        "dp_to_tp4_r0": repack_row(rc.moved_bytes, *fwd)}
+            del rc
+            torch.cuda.empty_cache()
         others = []
-        for name in ("llama8b_tp_b128", "llama70b_tp8_b256", "llama8b_tp4_longmix"):
+        for name in ("llama8b_tp_b128", "llama70b_tp8_b256", "llama8b_tp4_longmix") if want("other_workloads") else ():
             ow = wl.WORKLOADS[name]
             for tr in ow.views:
                 oc = harness.build_decode_case(ow, tr, n_copies=args.copies)
@@ -373,27 +386,31 @@ def main():
                                             "frac": round(oc.kv_bytes / k_ms / 1e6 / HBM_PEAK_GBPS, 4)}})
                 del oc, orun
                 torch.cuda.empty_cache()
-        extras["other_workloads"] = others
+        if want("other_workloads"):
+            extras["other_workloads"] = others
 
         # --- rows beyond the headline path, each against its own roofline -------------------------
         MFMA_BF16_PEAK_TFLOPS = 2500.0
-        mw = wl.WORKLOADS["llama8b_tp_b128"]
-        mc = harness.build_mixed_case(mw, 2, 0)
-        ms = harness.time_calls(mc.run, max(10, args.steps // 2), 5)
-        extras["mixed_layout_decode"] = {
-            "workload": mw.name, "what": "TP2 rank 0; every other sequence read in place from DP-layout blocks; one launch",
-            "us_per_layer": round(ms * 1e3, 2), "GBps": round(mc.kv_bytes / (ms * 1e-3) / 1e9, 1),
-            "pct_hbm_peak": round(100 * mc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
-        del mc
-        torch.cuda.empty_cache()
+        if want("mixed_layout_decode"):
+            mw = wl.WORKLOADS["llama8b_tp_b128"]
+            mc = harness.build_mixed_case(mw, 2, 0)
+            ms = harness.time_calls(mc.run, max(10, args.steps // 2), 5)
+            extras["mixed_layout_decode"] = {
+                "workload": mw.name, "what": "TP2 rank 0; every other sequence read in place from DP-layout blocks; one launch",
+                "us_per_layer": round(ms * 1e3, 2), "GBps": round(mc.kv_bytes / (ms * 1e-3) / 1e9, 1),
+                "pct_hbm_peak": round(100 * mc.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2)}
+            del mc
+            torch.cuda.empty_cache()
 
         pre = []
         w8 = wl.Workload("llama8b_recompute", 90, 32, 8, 128, 16, 8, "fixed", ())
-        for label, tr, ctx, ql in (("8 prompts of 4096 tokens, whole", (0, 1, 0), [4096] * 8, [4096] * 8),
-                                   ("8 prompts of 4096 tokens, whole", (1, 2, 0), [4096] * 8, [4096] * 8),
-                                   ("16 chunks of 512 tokens on 8192 cached", (0, 1, 0), [8192] * 16, [512] * 16),
-                                   ("1 chunk of 512 tokens on 131072 cached (key range split over workgroups)",
-                                    (0, 1, 0), [131072], [512])):
+        for case_no, (label, tr, ctx, ql) in enumerate((
+                ("8 prompts of 4096 tokens, whole", (0, 1, 0), [4096] * 8, [4096] * 8),
+                ("8 prompts of 4096 tokens, whole", (1, 2, 0), [4096] * 8, [4096] * 8),
+                ("16 chunks of 512 tokens on 8192 cached", (0, 1, 0), [8192] * 16, [512] * 16),
+                ("1 chunk of 512 tokens on 131072 cached (key range split over workgroups)", (0, 1, 0), [131072], [512]))):
+            if not want("paged_prefill_attn", case_no):
+                continue
             pc = harness.build_prefill_case(w8, tr, ctx, ql)
             for i in range(3):
                 pc.run(i)
@@ -410,7 +427,8 @@ def main():
                                      "frac": round(pc.flops / k_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}})
             del pc
             torch.cuda.empty_cache()
-        extras["paged_prefill_attn"] = pre
+        if pre:
+            extras["paged_prefill_attn"] = pre
 
         lin = []
         hq, hkv, d, hidden = 32, 8, 128, 4096
@@ -419,11 +437,15 @@ def main():
         n_w = 6   # distinct weights cycled through, so that no call finds its weight in the last-level cache
         wqkv = [torch.randn(((hq + 2 * hkv) * d, hidden), generator=g, device="cuda").to(torch.bfloat16) for _ in range(n_w)]
         wo = [torch.randn((hidden, hq * d), generator=g, device="cuda").to(torch.bfloat16) for _ in range(n_w)]
+        case_no = -1
         for M, m in ((64, 1), (64, 2), (128, 2), (256, 8)):
             x = torch.randn((M, hidden), generator=g, device="cuda").to(torch.bfloat16)
             a_full = torch.randn((M, hq * d), generator=g, device="cuda").to(torch.bfloat16)
             for name, view, xin, ws in (("qkv", kv.kv_weight_view_fused_qkv(hq, hkv, d, hidden, 0, m), x, wqkv),
                                         ("wo", kv.kv_weight_view_make(1, 0, m, hidden, hq * d), None, wo)):
+                case_no += 1
+                if not want("kv_linear_view", case_no):
+                    continue
                 if xin is None:
                     xin = a_full[:, :view.col_count]
                 out = torch.empty((M, view.n_rows), dtype=torch.bfloat16, device="cuda")
@@ -443,7 +465,8 @@ def main():
                             "roofline": {"bound": "hbm", "achieved": round(wbytes / k_ms / 1e6, 1), "peak": HBM_PEAK_GBPS,
                                          "unit": "GB/s", "frac": round(wbytes / k_ms / 1e6 / HBM_PEAK_GBPS, 4)},
                             "TFLOPs": round(2.0 * M * view.n_rows * view.col_count / k_ms / 1e9, 1)})
-        extras["kv_linear_view"] = lin
+        if lin:
+            extras["kv_linear_view"] = lin
         if args.library_context:
             extras["library_context"] = library_context(kv, wqkv, wo)
         result["extras"] = extras

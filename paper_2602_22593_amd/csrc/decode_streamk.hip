@@ -198,22 +198,6 @@ __device__ __forceinline__ void compute_tile(const tile_regs& t, const bf16x8 (&
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-// Development builds (-DKV_DECODE_TRACE) record when each wavefront passes the stages of the kernel.
-#ifdef KV_DECODE_TRACE
-#define KV_TRACE(a, w, k) \
-    do { if ((a).trace && (threadIdx.x & 63) == 0) (a).trace[(int64_t)(w) * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#define KV_TRACE_VAL(a, w, k, val) \
-    do { if ((a).trace && (threadIdx.x & 63) == 0) (a).trace[(int64_t)(w) * 8 + (k)] = (unsigned long long)(val); } while (0)
-#ifdef KV_TRACE_PROLOGUE
-#define KV_TRACE_PRO(a, w, k) KV_TRACE(a, w, k)
-#else
-#define KV_TRACE_PRO(a, w, k) do {} while (0)
-#endif
-#else
-#define KV_TRACE_PRO(a, w, k) do {} while (0)
-#define KV_TRACE(a, w, k) do {} while (0)
-#define KV_TRACE_VAL(a, w, k, val) do {} while (0)
-#endif
 
 // Where a wavefront's share starts: tiles [x0, x1) of the flattened batch, the first one being
 // tile `tile` of pair `pair` of sequence `s` (which has tiles_s tiles per pair); w numbers the
@@ -351,7 +335,6 @@ __device__ __forceinline__ splitter split_prologue(const kv_streamk_args& a, int
             s_wsum[kSkWaves + wave] = incl_ne;
         }
         __syncthreads();
-        KV_TRACE_PRO(a, blockIdx.x * kSkWaves + wave, 3);
         int before = 0, before_ne = 0;
         for (int w = 0; w < wave; ++w) {
             before += s_wsum[w];
@@ -377,7 +360,6 @@ __device__ __forceinline__ splitter split_prologue(const kv_streamk_args& a, int
             s_wpos[a.batch] = wpos(before + incl, before_ne + incl_ne);
         }
         __syncthreads();
-        KV_TRACE_PRO(a, blockIdx.x * kSkWaves + wave, 4);
     }
 
     // Nobody else writes the output rows of a sequence without tokens: the workgroups share them
@@ -396,7 +378,6 @@ __device__ __forceinline__ splitter split_prologue(const kv_streamk_args& a, int
                    ((unsigned long long)uniform((int)(w_all >> 32)) << 32) | (uint32_t)uniform((int)w_all)};
     sp.w = blockIdx.x * kSkWaves + wave;
     const tile_pos first = sx.tile_at(sx.range_u(sp.w));
-    KV_TRACE_PRO(a, blockIdx.x * kSkWaves + wave, 5);
     sp.x0 = first.x;
     sp.x1 = first.x;
     sp.s = first.s;
@@ -564,13 +545,6 @@ __device__ __forceinline__ void merge_pieces(const kv_streamk_args& a, int s, in
                 av[rr][j] = ld_coherent2(reinterpret_cast<const float*>(rec + off));
             }
         }
-#ifdef KV_DECODE_TRACE
-        if (r0 == 0) {
-            KV_TRACE(a, blockIdx.x * kSkWaves + (threadIdx.x >> 6), 7);   // loads issued
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            KV_TRACE_VAL(a, blockIdx.x * kSkWaves + (threadIdx.x >> 6), 6, __builtin_amdgcn_s_memrealtime());
-        }
-#endif
         const float m = mine ? ml[0] : kNegInf;   // (-inf also from a wavefront that had no tiles)
         const float m_new = fmaxf(m_run, group_max<RB>(m));
         const float ref = (m_new == kNegInf) ? 0.f : m_new;
@@ -614,12 +588,10 @@ __device__ __forceinline__ void merge_pieces(const kv_streamk_args& a, int s, in
 __device__ __forceinline__ void settle_pieces(const kv_streamk_args& a, const cut_pieces& cp, int lane, int w,
                                               kv_u32x4* stage)
 {
-    KV_TRACE(a, w, 2);
     if (!a.fused || cp.n == 0) return;
     // every partial this wavefront stored has reached the point of coherence
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    KV_TRACE(a, w, 3);
     unsigned long long seen0 = 0ull, seen1 = 0ull;
     if (lane == 0) {
         seen0 = __hip_atomic_fetch_add(a.pair_sync + ((int64_t)cp.s[0] * a.pairs + cp.sub[0]), cp.add[0],
@@ -634,7 +606,6 @@ __device__ __forceinline__ void settle_pieces(const kv_streamk_args& a, const cu
         const int s = k ? cp.s[1] : cp.s[0], sub = k ? cp.sub[1] : cp.sub[0];
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)seen);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(seen >> 32));
-        if (k == 0) KV_TRACE(a, w, 4);
         const unsigned long long now = (((unsigned long long)hi << 32) | lo) + add;
         const int count = (int)(now & 0xffffu);
         const int first = (int)((now >> kSyncFirstShift) & 0xffffffu), last = (int)(now >> kSyncLastShift);
@@ -655,7 +626,6 @@ __device__ __forceinline__ void settle_pieces(const kv_streamk_args& a, const cu
                 else merge_pieces<16, false>(a, s, sub, first - 1, last - 1, lane, stage);
         }
     }
-    KV_TRACE(a, w, 5);
 }
 
 // A wavefront without tiles (fewer tiles than wavefronts).  Its range is the empty one at tile x:
@@ -700,7 +670,6 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_streamk_kernel(kv_stream
     const int Hl = v.n_kv_local, G = a.group;
     kv_u32x4* kstage = s_kstage + wave * 512;
 
-    KV_TRACE(a, blockIdx.x * kSkWaves + wave, 0);
     split_pos sp;
     const splitter sx = split_prologue<5>(a, Hl, s_prefix, s_wpos, s_ctx, s_wsum, sp);
     int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hl = sp.pair, tile = sp.tile;
@@ -789,7 +758,6 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_streamk_kernel(kv_stream
         empty_wavefront(a, s_prefix, Hl, x1, w, lane, kstage);
         return;
     }
-    KV_TRACE(a, w, 1);
 
     for (;;) {
         const int seg_end = min(tiles_s, tile + (x1 - x0));
@@ -1023,7 +991,6 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
     const int P = a.pairs, C = a.cols, G = a.group;
     kv_u32x4* kstage = s_kstage + wave * 512;
 
-    KV_TRACE(a, blockIdx.x * kSkWaves + wave, 0);
     split_pos sp;
     const splitter sx = split_prologue<TSHIFT>(a, P, s_prefix, s_wpos, s_ctx, s_wsum, sp);
     int x0 = sp.x0, s = sp.s, tiles_s = sp.tiles_s, hg = sp.pair, tile = sp.tile;
@@ -1119,7 +1086,6 @@ __global__ __launch_bounds__(kSkThreads, 1) void decode_wide_kernel(kv_streamk_a
         empty_wavefront(a, s_prefix, P, x1, w, lane, kstage);
         return;
     }
-    KV_TRACE(a, w, 1);
 
     for (;;) {
         const int seg_end = min(tiles_s, tile + (x1 - x0));
@@ -1202,11 +1168,12 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     __shared__ float s_max[32];
     __shared__ float s_acc[8 * D];
     __shared__ float s_l[32];
-    const int n = a.ctx_lens[s];
     uint16_t* dst = a.out + ((int64_t)s * v.n_q_local + qi) * D;
     const int hl = qi / G, g = qi - hl * G;
-    // numbers of the wavefronts that held the pair's first and last piece, left by the main kernel
+    // the context length, and the numbers of the wavefronts that held the pair's first and last piece,
+    // left by the main kernel (both requested before either is looked at: one round trip, not two)
     const int2 ends = *reinterpret_cast<const int2*>(a.pair_desc + ((int64_t)s * Hl + hl) * 2);
+    const int n = a.ctx_lens[s];
     if (n == 0) {
         if (z == 0 && tid < D) dst[tid] = 0;
         return;
@@ -1226,18 +1193,19 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
     // to the common maximum and summed through LDS
     float mr = kNegInf, ll = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    // (four pieces requested at a time: one memory round trip per four pieces, not one per piece)
-    for (int w0 = w_first + slice; w0 <= w_last; w0 += 4 * nsl) {
-        float2 ml[4];
-        f32x4 part[4];
+    constexpr int kBatch = 8;
+    // (eight pieces requested at a time: one memory round trip per eight pieces, not one per piece)
+    for (int w0 = w_first + slice; w0 <= w_last; w0 += kBatch * nsl) {
+        float2 ml[kBatch];
+        f32x4 part[kBatch];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kBatch; ++j) {
             const int64_t rec = (min(w0 + j * nsl, w_last) + pair) * G + g;
             ml[j] = *reinterpret_cast<const float2*>(a.part_ml + rec * 2);
             part[j] = *reinterpret_cast<const f32x4*>(a.part_acc + rec * D + col0 + cg * 4);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kBatch; ++j) {
             if (w0 + j * nsl > w_last) break;
             // (a wavefront that had no tiles left m = -inf, l = 0 and zeros: its weight comes out as 0)
             const float mn = fmaxf(mr, ml[j].x);
@@ -1268,10 +1236,6 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
 
 }  // namespace
 
-#ifdef KV_DECODE_TRACE
-static unsigned long long* g_decode_trace = nullptr;
-extern "C" void kv_debug_decode_trace(void* device_buffer) { g_decode_trace = (unsigned long long*)device_buffer; }
-#endif
 
 // Adjacent KV heads one wavefront takes (1: the one-head kernel).  With HPW heads the HPW * G
 // query rows of a pair must fit the 16 columns of the matrix-core tile.
@@ -1358,9 +1322,6 @@ int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, h
         const int64_t pc = kv_option_piece_cost();
         a.piece_units = (int32_t)(pc < 0 ? kDefaultPieceUnits : pc);
     }
-#ifdef KV_DECODE_TRACE
-    a.trace = g_decode_trace;
-#endif
     const dim3 grid((unsigned)(a.n_waves / kSkWaves)), block(kSkThreads);
     // (while kv_profile is on, each kernel is launched with a pair of events that take its own start
     // and end times)

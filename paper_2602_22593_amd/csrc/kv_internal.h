@@ -123,9 +123,6 @@ struct kv_streamk_args {
                           // (read by the merge kernel; unused when the main kernel combines the pieces)
     unsigned long long* pair_sync;  // [batch * pairs] arrival words of the pairs, zero between calls
     int32_t fused;        // 1: the last piece of a pair to arrive combines them all (no merge kernel)
-#ifdef KV_DECODE_TRACE
-    unsigned long long* trace;   // [n_waves][8] timestamps, development builds only
-#endif
     const int32_t* view_ids;  // [batch] index into lay[] per sequence, or null: every sequence under v
     int32_t n_views;
     kv_layout_dev lay[KV_MAX_MIXED_VIEWS];
