@@ -90,22 +90,28 @@ __device__ __forceinline__ void add_slices(const linear_args& p, int64_t wg_tile
 {
     const int r = lane & 15, quad = lane >> 4;
     const int64_t slice_step = wg_tiles * (NB * kColBlocks) * 256;   // floats between two slices
+    const float* src = p.part + ((wg_tile * (NB * kColBlocks) + wave * NB) * 64 + lane) * 4;
+    f32x4 sum[NB];
 #pragma unroll
-    for (int t = 0; t < NB; ++t) {
-        const int tile = wave * NB + t;
-        const float* src = p.part + ((wg_tile * (NB * kColBlocks) + tile) * 64 + lane) * 4;
-        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-        for (int z0 = 0; z0 < p.splits; z0 += 4) {   // four slices requested at a time
-            f32x4 v[4];
+    for (int t = 0; t < NB; ++t) sum[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // four slices of all this wavefront's tiles are requested before any is added: one memory round
+    // trip per four slices
+    for (int z0 = 0; z0 < p.splits; z0 += 4) {
+        f32x4 v[NB][4];
+#pragma unroll
+        for (int t = 0; t < NB; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                v[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)min(z0 + j, p.splits - 1) * slice_step);
+                v[t][j] = *reinterpret_cast<const f32x4*>(src + t * 256 + (int64_t)min(z0 + j, p.splits - 1) * slice_step);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (z0 + j < p.splits) sum += v[j];
+        for (int j = 0; j < 4; ++j) {
+            if (z0 + j >= p.splits) break;
+#pragma unroll
+            for (int t = 0; t < NB; ++t) sum[t] += v[t][j];
         }
-        store_tile<NB>(p, sum, tile, m0, blk0, n_blocks, r, quad);
     }
+#pragma unroll
+    for (int t = 0; t < NB; ++t) store_tile<NB>(p, sum[t], wave * NB + t, m0, blk0, n_blocks, r, quad);
 }
 
 template <int NB>
