@@ -341,9 +341,10 @@ int kv_validate_tables(const kv_view* view, int64_t n_pool_blocks, const int32_t
  *   "piece_cost"     even-split decode kernels: what the start of a (sequence, head group) pair counts
  *                    for when the work is cut over the wavefronts, in eighths of a 16 KiB tile
  *                    (0..64; -1 = the library's default, 16)
- *   "linear_splits"  workgroups sharing the input dimension of one output tile in kv_linear_view
- *                    (1..16; capped at the number of 128-wide slabs); kv_linear_view_workspace_bytes
- *                    follows the option, so size the workspace after setting it
+ *   "linear_splits"  kv_linear_view cuts the input dimension into at least this many slices (1..16;
+ *                    a slice is never longer than 1024 input features nor shorter than 128);
+ *                    kv_linear_view_workspace_bytes follows the option, so size the workspace after
+ *                    setting it
  * Returns KV_ERR_INVALID_ARG for an unknown key or an illegal value. */
 int kv_set_option(const char* key, int64_t value);
 int64_t kv_get_option(const char* key);
