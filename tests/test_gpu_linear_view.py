@@ -106,3 +106,24 @@ def test_every_cut_of_the_input_dimension(slabs, splits):
     finally:
         kv.kv_set_option("linear_splits", 0)
     check(y.cpu().view(torch.int16).numpy().view(np.uint16), x, w, ov, f"slabs {slabs} splits {splits}")
+
+
+@pytest.mark.parametrize("M,N,K,what", [
+    (64, 8256, 4096, "8 row blocks per workgroup, four slices; the last workgroup of a column has 4 of its 8 blocks"),
+    (64, 6208, 4096, "6 row blocks, four slices; the last workgroup has 4 of its 6"),
+    (64, 4160, 4096, "4 row blocks, four slices"),
+    (128, 1600, 4096, "3 row blocks, two batch tiles; the last workgroup has 1 of its 3"),
+    (256, 1344, 2048, "2 row blocks, four batch tiles, two slices"),
+    (40, 832, 640, "1 row block, one slice of 5 slabs: wavefront 0 has two slabs, the others one"),
+    (200, 320, 1152, "1 row block, four batch tiles, slices of 8 slabs and of 1"),
+])
+def test_every_rows_per_workgroup_shape(M, N, K, what):
+    """Shapes that make the library pick each of its row-blocks-per-workgroup instantiations (8, 6, 4,
+    3, 2, 1), with block counts that do not divide evenly (trailing blocks are requested from idle
+    addresses and multiplied by zero) and slices whose slab count is not a multiple of the four
+    wavefronts.  Rows and columns are a sub-range of a larger stored weight."""
+    x, w = bits((M, K), 60 + M), bits((N + 128, K + 256), 61 + (N % 97))
+    ov = ow.WeightView(((64, N),), 128, K)
+    y = kv.kv_linear_view(dev(x), dev(w), gpu_view(ov))
+    torch.cuda.synchronize()
+    check(y.cpu().view(torch.int16).numpy().view(np.uint16), x, w, ov, what)
