@@ -14,29 +14,34 @@
 //
 // So x stays put.  The input dimension is cut into slices of at most 8 slabs of 128 input features,
 // and a workgroup owns one slice x 64 batch rows x NB blocks of 16 logical weight rows.  Each of its
-// four wavefronts takes two slabs of the slice (w and w + 4) and loads its 64 x 256 piece of x ONCE,
-// straight into the arrangement of the matrix instruction's B operand, where it stays for the whole
-// kernel (128 registers).  Then the wavefront walks the NB row blocks: a block's 16 rows x 2 slabs
-// are requested four rows of 256 contiguous bytes per load instruction (64-byte pieces of a row per
-// instruction, as the operand arrangement would ask for, halve the rate at which HBM delivers the
-// weights), two row blocks ahead of the arithmetic, pass through a private LDS area of the wavefront
-// (XOR-swizzled so that the row-wise writes and the operand-wise reads are free of bank conflicts)
-// and come back as A operands:
+// four wavefronts takes two slabs of the slice (w and w + 4) and loads its 64 x 256 piece of x ONCE
+// (row-order loads, passed through its private LDS area into the arrangement of the matrix
+// instruction's B operand), where it stays for the whole kernel (128 registers).  Then the wavefront
+// walks the NB row blocks: a block's 16 rows x 2 slabs are requested four rows of 256 contiguous
+// bytes per load instruction (64-byte pieces of a row per instruction, as the operand arrangement
+// would ask for, halve the rate at which HBM delivers the weights), two row blocks ahead of the
+// arithmetic, pass through the private LDS area (XOR-swizzled so that the row-wise writes and the
+// operand-wise reads are free of bank conflicts) and come back as A operands:
 //   y^T[weight row][batch row] += W[row][k .. k + 32) . x[batch row][k .. k + 32)
 // with 16x16x32 bf16 MFMA, fp32 accumulation.  The walk is straight-line code (NB is a template
 // parameter): the compiler's count of outstanding requests is then exact and a row block waits for
-// its own rows only.  No workgroup barrier until the end, where the four wavefronts add their
-// accumulators through LDS.  With one slice the sums are rounded to bf16 and stored; with several,
-// each workgroup leaves an fp32 partial tile in the workspace and a second, small kernel adds the
-// slices in a fixed order (deterministic) and rounds once.  NB is chosen so that the launch has at
-// least one workgroup per compute unit.
+// its own rows only.  All of x and the first two row blocks are requested before anything is waited
+// for (48 requests): x, mostly from L2, is back first and is arranged while the weight rows are
+// still on their way from HBM.  Registers decide how far ahead the requests can run: the matrix
+// instructions take A and B operands from the 256 architectural registers only, and once x (128),
+// the row blocks in flight and the raw x rows add up to more than that the compiler parks arrived
+// data in accumulator registers, which makes it wait for that data in the middle of the request
+// sequence (three row blocks ahead measured 1.2-2 us slower than two for this reason).  No workgroup
+// barrier until the end, where the four wavefronts add their accumulators through LDS.  With one
+// slice the sums are rounded to bf16 and stored; with several, each workgroup leaves an fp32 partial
+// tile in the workspace and a second, small kernel adds the slices in a fixed order (deterministic)
+// and rounds once.  NB is chosen so that the launch has at least one workgroup per compute unit.
 //
-// Where the time goes (time stamps inside the kernel, fused QKV weight of 6144 x 4096 at M = 64,
-// 16.8 us for the first kernel): the first weight rows and x are in the registers 5.9 us after the
-// first wavefront starts (three dependent cold accesses: kernel arguments, first rows from HBM, x),
-// the six row blocks are done at 10.5 us (the 50 MB stream averages 5 TB/s from the first request
-// on), the accumulators are added and stored at 12.3 us; the rest is the launch and the write-back
-// of the partial tiles at the kernel's end.  The second kernel adds 3.7 us.
+// Measured, fused QKV weight of 6144 x 4096 at M = 64: 14.0 us for the first kernel, 4.1 us for the
+// second; in a replayed graph 16.7 us per call (W^O 4096 x 4096: 12.7 us).  Time stamps inside an
+// earlier build of the first kernel (16.8 us): first weight rows and x in the registers 5.9 us
+// after the first wavefront starts, the six row blocks done at 10.5 us, accumulators added and
+// stored at 12.3 us; the rest is the launch and the write-back at the kernel's end.
 #include <string.h>
 #include <hip/hip_ext.h>
 
@@ -117,7 +122,7 @@ __device__ __forceinline__ void add_slices(const linear_args& p, int64_t wg_tile
 template <int NB>
 __global__ __launch_bounds__(kThreads, 1) void linear_slice_kernel(linear_args p)
 {
-    constexpr int NR = 3;             // row blocks requested ahead
+    constexpr int NR = 2;             // row blocks requested ahead
     constexpr int kStagePieces = 2 * 256;                       // per wavefront: 2 slabs x 16 rows x 16 pieces
     constexpr int kRedPieces = kWaves * NB * kColBlocks * 64;   // all accumulators, one f32x4 per lane each
     constexpr int kLdsPieces = kWaves * kStagePieces > kRedPieces ? kWaves * kStagePieces : kRedPieces;
@@ -175,10 +180,6 @@ __global__ __launch_bounds__(kThreads, 1) void linear_slice_kernel(linear_args p
             }
         }
     };
-    // the first weight rows are requested before x: they come from HBM, x mostly from L2
-#pragma unroll
-    for (int b = 0; b < NR && b < NB; ++b) issue(b, b);
-
     // x, once: fetched like weight rows (16 batch rows x 1 slab at a time), passed through the private
     // LDS area and kept as B operands: x_reg[t][kk][cb] = the 16 bytes of batch row 16 cb + r, 32-wide
     // step kk of slab t, that lane (r, quad) contributes (rows past M repeat the last one)
@@ -195,6 +196,10 @@ __global__ __launch_bounds__(kThreads, 1) void linear_slice_kernel(linear_args p
                 for (int t = 0; t < 2; ++t)
                     raw[t][cb][i] = *reinterpret_cast<const kv_u32x4*>(xbase + koff[t] + xlane);
             }
+        // the first weight rows are requested right behind x: x (mostly from L2) is back first and is
+        // arranged while the weight rows are still on their way from HBM
+#pragma unroll
+        for (int b = 0; b < NR && b < NB; ++b) issue(b, b);
 #pragma unroll
         for (int cb = 0; cb < kColBlocks; ++cb) {
 #pragma unroll
