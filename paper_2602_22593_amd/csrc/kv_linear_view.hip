@@ -38,10 +38,11 @@
 // and rounds once.  NB is chosen so that the launch has at least one workgroup per compute unit.
 //
 // Measured, fused QKV weight of 6144 x 4096 at M = 64: 14.0 us for the first kernel, 4.1 us for the
-// second; in a replayed graph 16.7 us per call (W^O 4096 x 4096: 12.7 us).  Time stamps inside an
-// earlier build of the first kernel (16.8 us): first weight rows and x in the registers 5.9 us
-// after the first wavefront starts, the six row blocks done at 10.5 us, accumulators added and
-// stored at 12.3 us; the rest is the launch and the write-back at the kernel's end.
+// second; in a replayed graph 16.7 us per call (W^O 4096 x 4096: 12.7 us).  Time stamps inside the
+// first kernel: x in the registers 3.2 us after the first wavefront starts, the six row blocks done
+// at 8.9 us (about 1 us per block: the 50 MB stream runs at 6 TB/s from the first request on), the
+// accumulators added and stored at 10.5 us; the rest is the launch and the write-back at the
+// kernel's end.
 #include <string.h>
 #include <hip/hip_ext.h>
 
@@ -88,7 +89,8 @@ __device__ __forceinline__ void store_tile(const linear_args& p, f32x4 sum, int 
     *reinterpret_cast<uint2*>(p.y + (int64_t)m * p.ldy + (16 * (blk0 + b) + 4 * quad)) = pk;
 }
 
-// The partial tiles of all slices of one workgroup tile, added in slice order and stored.  Wavefront w takes tiles w NB .. w NB + NB - 1.
+// The partial tiles of all slices of one workgroup tile, added in slice order and stored.  Wavefront
+// w takes tiles w NB .. w NB + NB - 1.
 template <int NB>
 __device__ __forceinline__ void add_slices(const linear_args& p, int64_t wg_tiles, int64_t wg_tile, int m0, int blk0,
                                            int n_blocks, int wave, int lane)
