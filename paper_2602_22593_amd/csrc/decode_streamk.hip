@@ -1239,14 +1239,18 @@ __global__ __launch_bounds__(256) void decode_streamk_merge_kernel(kv_streamk_ar
 
 // Adjacent KV heads one wavefront takes (1: the one-head kernel).  With HPW heads the HPW * G
 // query rows of a pair must fit the 16 columns of the matrix-core tile.
-static int wide_heads(const kv_view* view)
+static int wide_heads(const kv_view* view, int batch, int n_waves)
 {
     if (kv_option_heads_per_wave() == 1) return 1;
-    // measured: a gain of 2-5 % where the token rows hold more heads than one wavefront takes or
-    // the query rows fill the 16 columns; a small loss for two heads of a two-head row otherwise
+    // measured: a gain of 2-5 % where a wavefront then reads whole token rows or the query rows fill
+    // the 16 columns
     const int G = view->group, Hl = view->n_kv_local;
     if (G <= 4 && Hl % 4 == 0) return 4;
     if (G > 4 && G <= 8 && Hl % 2 == 0 && Hl >= 4) return 2;
+    // two-head rows with small groups (TP4 of the 8B shape): both heads of the row, 2.5 % faster than
+    // one on a batch of many sequences (95.5 -> 93.1 us at batch 128); not where a few very long
+    // sequences are cut into long piece lists, whose records it doubles (60.3 against 59.9 us)
+    if (G <= 4 && Hl % 2 == 0 && (int64_t)batch * Hl * kMergeLong > n_waves) return 2;
     return 1;
 }
 
@@ -1279,7 +1283,7 @@ size_t kv_streamk_workspace_bytes(const kv_view* view, int batch, int n_waves)
 
 int kv_streamk_launch(kv_streamk_args a, const kv_view* view, void* workspace, hipStream_t st)
 {
-    const int hpw = wide_heads(view);
+    const int hpw = wide_heads(view, a.batch, a.n_waves);
     a.heads_per_wave = hpw;
     a.pairs = view->n_kv_local / hpw;
     a.cols = view->group * hpw;
